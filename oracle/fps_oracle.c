@@ -1,0 +1,281 @@
+/*
+ * CPU oracle for farthest point sampling (FPS) and the FlashFPS variants.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what
+ * the GPU library must compute.  It is used by the tests, by the smoke check
+ * and by the benchmark's CPU-baseline leg.  The product path never calls it,
+ * and it shares no code, header, table or helper with the HIP sources.
+ *
+ * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC
+ * (contraction must stay off: a fused multiply-add changes low bits of the
+ * squared distance and therefore changes picks).
+ *
+ * Conventions fixed for the whole build (the paper leaves them open):
+ *   - coordinates are fp32, array-of-structs [N][3]; indices are int32;
+ *   - squared Euclidean distance  ((dx*dx) + (dy*dy)) + (dz*dz), every
+ *     operation rounded to fp32 (round-to-nearest-even), no FMA.  Squared
+ *     and true distance order points identically, so Eq. 1's norm is never
+ *     taken inside the loop;
+ *   - running minimum distance starts at +inf;
+ *   - the argmax runs over ALL points (Eq. 2's form of the rule): a sampled
+ *     point has minimum distance 0 and can only win when every point has 0;
+ *   - ties go to the lowest index (lowest position in the array FPS runs on).
+ *
+ * Every function is pinned by tests that do not use this file's own
+ * arithmetic: hand-worked lattice sequences, a from-scratch brute force of
+ * Eq. 1 in exact integer arithmetic, the p = 0 and prefix-equivalence
+ * identities of Sec. 3.2 / 3.3, and closed-form index sets for the
+ * pruning and fill rules.  Nothing here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_FLAG_CP 1u /* candidate pruning  (Alg. 1, step "P' <- UniformSample") */
+#define ORACLE_FLAG_IP 2u /* iteration pruning  (Alg. 1, step "k <- (1-p) M1")       */
+
+#define ORACLE_MODE_CACHED 0      /* Alg. 1, layers 2..L: prefixes of the cached P1 */
+#define ORACLE_MODE_CHAIN 1       /* Sec. 3.3: every layer runs its own FPS          */
+
+static float sqdist(const float *a, const float *b)
+{
+    float dx = a[0] - b[0];
+    float dy = a[1] - b[1];
+    float dz = a[2] - b[2];
+    float xx = dx * dx;
+    float yy = dy * dy;
+    float zz = dz * dz;
+    float s = xx + yy;
+    return s + zz;
+}
+
+/*
+ * Exact FPS, Eq. 1 (Sec. 3.1), as the loop Sec. 1 describes: after each pick,
+ * every point's minimum distance to the sampled set is refreshed with its
+ * distance to the newest sample, then the point with the largest minimum
+ * distance is the next pick.
+ *
+ * idx[0] = start; idx[1..M-1] = picks.  maxdist (optional) receives the
+ * squared minimum distance each pick had when it was chosen; maxdist[0] = +inf.
+ * Returns 0, or -1 on invalid arguments.
+ */
+int oracle_fps_exact(const float *xyz, int N, int M, int start, int32_t *idx, float *maxdist)
+{
+    if (!xyz || !idx || N < 1 || M < 1 || M > N || start < 0 || start >= N)
+        return -1;
+    float *mind = (float *)malloc((size_t)N * sizeof(float));
+    if (!mind)
+        return -2;
+    for (int i = 0; i < N; ++i)
+        mind[i] = INFINITY;
+    idx[0] = start;
+    if (maxdist)
+        maxdist[0] = INFINITY;
+    int last = start;
+    for (int k = 1; k < M; ++k) {
+        const float *q = xyz + 3 * (size_t)last;
+        int best = -1;
+        float bestd = 0.0f;
+        for (int i = 0; i < N; ++i) {
+            float d = sqdist(xyz + 3 * (size_t)i, q);
+            if (d < mind[i])
+                mind[i] = d;
+            if (best < 0 || mind[i] > bestd) { /* strict >: lowest index keeps a tie */
+                best = i;
+                bestd = mind[i];
+            }
+        }
+        idx[k] = best;
+        if (maxdist)
+            maxdist[k] = bestd;
+        last = best;
+    }
+    free(mind);
+    return 0;
+}
+
+/* ceil(a * num / den) in 64-bit integers */
+static int64_t ceil_frac(int64_t a, int64_t num, int64_t den)
+{
+    return (a * num + den - 1) / den;
+}
+
+/*
+ * Sizes of FPS-Prune (Alg. 1, layer 1; Sec. 3.2).  keep_num/keep_den = 1 - p.
+ *   N' = ceil(N * keep) if candidate pruning is on, else N
+ *   k  = ceil(M * keep) if iteration pruning is on, else M
+ *   R  = M - k  random-fill picks (= floor(p * M) when IP is on)
+ * Returns 0, or -1 when the ratio is outside (0, 1] or k > N'.
+ */
+int oracle_prune_sizes(int N, int M, int keep_num, int keep_den, unsigned flags,
+                       int *Nc, int *k, int *R)
+{
+    if (N < 1 || M < 1 || M > N || keep_num < 1 || keep_den < 1 || keep_num > keep_den)
+        return -1;
+    int64_t nc = (flags & ORACLE_FLAG_CP) ? ceil_frac(N, keep_num, keep_den) : N;
+    int64_t kk = (flags & ORACLE_FLAG_IP) ? ceil_frac(M, keep_num, keep_den) : M;
+    if (kk < 1 || kk > nc)
+        return -1;
+    *Nc = (int)nc;
+    *k = (int)kk;
+    *R = M - (int)kk;
+    return 0;
+}
+
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * Candidate list of candidate pruning: an index-uniform subsample of N' of the
+ * N points, shifted so that it contains `start`, kept in ascending index order.
+ *   cand = sort{ (start + floor(j * N / N')) mod N : j = 0..N'-1 }
+ * *start_pos receives the position of `start` inside cand.
+ */
+int oracle_candidates(int N, int Nc, int start, int32_t *cand, int *start_pos)
+{
+    if (N < 1 || Nc < 1 || Nc > N || start < 0 || start >= N)
+        return -1;
+    for (int j = 0; j < Nc; ++j)
+        cand[j] = (int32_t)(((int64_t)start + ((int64_t)j * N) / Nc) % N);
+    qsort(cand, (size_t)Nc, sizeof(int32_t), cmp_i32);
+    *start_pos = -1;
+    for (int j = 0; j < Nc; ++j)
+        if (cand[j] == start)
+            *start_pos = j;
+    return *start_pos < 0 ? -1 : 0;
+}
+
+/*
+ * FPS-Prune (Alg. 1, layer 1).  idx[0..k-1] = FPS order on the candidate
+ * cloud mapped back to indices of the full cloud; idx[k..M-1] = fill picks:
+ * with free = ascending list of the N - k indices not picked by FPS,
+ *   fill[j] = free[ floor(j * (N - k) / R) ],  j = 0..R-1.
+ * The fill is drawn from the full cloud, not from the candidate cloud.
+ */
+int oracle_fps_prune(const float *xyz, int N, int M, int start, int keep_num, int keep_den,
+                     unsigned flags, int32_t *idx, int *k_out)
+{
+    int Nc, k, R;
+    if (!xyz || !idx || start < 0 || start >= N)
+        return -1;
+    if (oracle_prune_sizes(N, M, keep_num, keep_den, flags, &Nc, &k, &R))
+        return -1;
+    int32_t *cand = (int32_t *)malloc((size_t)Nc * sizeof(int32_t));
+    float *cxyz = (float *)malloc((size_t)Nc * 3 * sizeof(float));
+    int32_t *loc = (int32_t *)malloc((size_t)k * sizeof(int32_t));
+    unsigned char *taken = (unsigned char *)calloc((size_t)N, 1);
+    int32_t *freelist = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+    int rc = -2, spos = 0;
+    if (!cand || !cxyz || !loc || !taken || !freelist)
+        goto done;
+    if (oracle_candidates(N, Nc, start, cand, &spos)) {
+        rc = -1;
+        goto done;
+    }
+    for (int j = 0; j < Nc; ++j)
+        memcpy(cxyz + 3 * (size_t)j, xyz + 3 * (size_t)cand[j], 3 * sizeof(float));
+    rc = oracle_fps_exact(cxyz, Nc, k, spos, loc, NULL);
+    if (rc)
+        goto done;
+    for (int j = 0; j < k; ++j) {
+        idx[j] = cand[loc[j]];
+        taken[idx[j]] = 1;
+    }
+    {
+        int64_t nfree = 0;
+        for (int i = 0; i < N; ++i)
+            if (!taken[i])
+                freelist[nfree++] = i;
+        for (int j = 0; j < R; ++j)
+            idx[k + j] = freelist[((int64_t)j * nfree) / R];
+    }
+    if (k_out)
+        *k_out = k;
+    rc = 0;
+done:
+    free(cand);
+    free(cxyz);
+    free(loc);
+    free(taken);
+    free(freelist);
+    return rc;
+}
+
+/*
+ * Hierarchical stage chain (Alg. 1; Sec. 3.3).  Ms[0] >= Ms[1] >= ... >= Ms[L-1].
+ * Layer 1 is oracle_fps_prune with Ms[0] (exact FPS when keep = 1/1).
+ *   CACHED: layer l = first Ms[l] entries of layer 1 (Alg. 1, layers 2..L).
+ *   CHAIN : layer l = FPS over the points of layer l-1 stored in sample
+ *           order, started at position 0, Ms[l] picks, mapped back to indices
+ *           of the full cloud (the independent per-layer FPS of Sec. 3.3).
+ * out holds the layers back to back: layer l at offset Ms[0] + ... + Ms[l-1].
+ */
+int oracle_fps_stages(const float *xyz, int N, int L, const int *Ms, int start, int keep_num,
+                      int keep_den, unsigned flags, int mode, int32_t *out)
+{
+    if (!xyz || !Ms || !out || L < 1)
+        return -1;
+    for (int l = 1; l < L; ++l)
+        if (Ms[l] > Ms[l - 1] || Ms[l] < 1)
+            return -1;
+    int rc = oracle_fps_prune(xyz, N, Ms[0], start, keep_num, keep_den, flags, out, NULL);
+    if (rc)
+        return rc;
+    size_t off = (size_t)Ms[0];
+    const int32_t *prev = out;
+    for (int l = 1; l < L; ++l) {
+        int32_t *cur = out + off;
+        if (mode == ORACLE_MODE_CACHED) {
+            memcpy(cur, out, (size_t)Ms[l] * sizeof(int32_t));
+        } else {
+            int Np = Ms[l - 1];
+            float *pxyz = (float *)malloc((size_t)Np * 3 * sizeof(float));
+            int32_t *loc = (int32_t *)malloc((size_t)Ms[l] * sizeof(int32_t));
+            if (!pxyz || !loc) {
+                free(pxyz);
+                free(loc);
+                return -2;
+            }
+            for (int j = 0; j < Np; ++j)
+                memcpy(pxyz + 3 * (size_t)j, xyz + 3 * (size_t)prev[j], 3 * sizeof(float));
+            rc = oracle_fps_exact(pxyz, Np, Ms[l], 0, loc, NULL);
+            for (int j = 0; rc == 0 && j < Ms[l]; ++j)
+                cur[j] = prev[loc[j]];
+            free(pxyz);
+            free(loc);
+            if (rc)
+                return rc;
+        }
+        prev = cur;
+        off += (size_t)Ms[l];
+    }
+    return 0;
+}
+
+/*
+ * Coverage radius of a sampled set over the full cloud:
+ *   R_P(S) = sqrt( max_{p in P} min_{q in S} d2(p, q) ),
+ * d2 in fp32 as above, the square root in double.  Used to state how far a
+ * pruned or cached sample set is from exact FPS.
+ */
+double oracle_coverage_radius(const float *xyz, int N, const int32_t *sel, int S)
+{
+    if (!xyz || !sel || N < 1 || S < 1)
+        return -1.0;
+    float worst = 0.0f;
+    for (int i = 0; i < N; ++i) {
+        float m = INFINITY;
+        for (int s = 0; s < S; ++s) {
+            float d = sqdist(xyz + 3 * (size_t)i, xyz + 3 * (size_t)sel[s]);
+            if (d < m)
+                m = d;
+        }
+        if (m > worst)
+            worst = m;
+    }
+    return sqrt((double)worst);
+}
