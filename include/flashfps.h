@@ -1,0 +1,150 @@
+/*
+ * flashfps.h -- C ABI of the MI355X (gfx950) farthest-point-sampling library.
+ *
+ * The library computes farthest point sampling (FPS) as the FlashFPS paper
+ * states it: exact FPS (Sec. 3.1, Eq. 1), FPS-Prune (Sec. 3.2; Alg. 1,
+ * layer 1) and the hierarchical stage chain with or without FPS-Cache
+ * (Sec. 3.3; Alg. 1, layers 2..L).
+ *
+ * Conventions shared by every entry point
+ *   - "d_" arguments are DEVICE pointers, everything else is host data.
+ *   - Clouds are fp32 array-of-structs: d_xyz[b][i][0..2], b < B, i < N,
+ *     densely packed ([B][N][3]); coordinates must be finite.
+ *   - Indices are int32 positions in [0, N) of the caller's cloud, also for
+ *     pruned and chained variants.
+ *   - Distance is the squared Euclidean distance ((dx*dx)+(dy*dy))+(dz*dz)
+ *     with every operation rounded to fp32 and no fused multiply-add; the
+ *     running minimum starts at +inf; the argmax runs over all points and a
+ *     tie goes to the lowest index.  With these rules the result is unique,
+ *     independent of the launch shape, and identical from run to run.
+ *   - Ownership: the caller owns every buffer.  The library allocates no
+ *     device memory and keeps no mutable global state; calls on different
+ *     streams are independent provided they use different workspaces.
+ *   - Asynchrony: work is enqueued on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream) and the call returns without
+ *     synchronising.  Outputs are valid once the stream has been synchronised.
+ *   - Errors: 0 on success, a negative FFPS_ERR_* code otherwise.  Arguments
+ *     are validated on the host before anything is enqueued, so an invalid
+ *     call has no effect on the device.
+ */
+#ifndef FLASHFPS_H
+#define FLASHFPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FFPS_OK 0
+#define FFPS_ERR_INVALID_ARG (-1)         /* null pointer, size out of range, M > N, bad ratio ... */
+#define FFPS_ERR_WORKSPACE_TOO_SMALL (-2) /* ws_bytes < ffps_workspace_bytes(...)                  */
+#define FFPS_ERR_UNSUPPORTED_DEVICE (-3)  /* current device is not gfx950                          */
+#define FFPS_ERR_LAUNCH_FAILED (-4)       /* a HIP call failed                                     */
+#define FFPS_ERR_TIMEOUT (-5)             /* a kernel gave up waiting for another workgroup        */
+#define FFPS_ERR_UNSUPPORTED_SIZE (-6)    /* the requested kernel variant cannot hold this N       */
+
+/* FPS-Prune switches (Alg. 1, layer 1). */
+#define FFPS_FLAG_CP 1u /* candidate pruning: FPS sees only N' = ceil(N * keep) points      */
+#define FFPS_FLAG_IP 2u /* iteration pruning: FPS stops after k = ceil(M * keep) picks       */
+
+/* How layers 2..L of a stage chain are produced. */
+#define FFPS_MODE_CACHED 0 /* FPS-Cache: prefixes of layer 1 (Alg. 1, layers 2..L)           */
+#define FFPS_MODE_CHAIN 1  /* every layer runs its own FPS on the previous layer (Sec. 3.3)  */
+
+/* Kernel variant; AUTO picks by (B, N). */
+#define FFPS_VARIANT_AUTO 0
+#define FFPS_VARIANT_WG 1     /* one workgroup per cloud, points resident in registers       */
+#define FFPS_VARIANT_GRID 2   /* one cloud across all CUs, points resident in registers      */
+#define FFPS_VARIANT_STREAM 3 /* one cloud across all CUs, points streamed from HBM per pass */
+/* Benchmarking knob for the multi-workgroup variants: cap on the picks accepted
+ * per exchange round (1 = one pick per pass over the points; 0 = library
+ * default).  The result never depends on it. */
+#define FFPS_VARIANT_WITH_PICKS(variant, picks) ((variant) | ((picks) << 8))
+
+/* Library version: major * 10000 + minor * 100 + patch.  Host only. */
+int ffps_version(void);
+
+/* Static, NUL-terminated description of an FFPS_* code.  Host only. */
+const char *ffps_strerror(int code);
+
+/*
+ * Sizes of FPS-Prune for pruning ratio p, given as keep_num/keep_den = 1 - p
+ * (Alg. 1: N' = (1-p) N, k = (1-p) M1, p M1 fill picks; both products are
+ * rounded up, in 64-bit integers):
+ *   *Nc = candidate count N' (N when FFPS_FLAG_CP is off)
+ *   *k  = FPS picks          (M when FFPS_FLAG_IP is off)
+ *   *R  = M - k fill picks
+ * Host only.  FFPS_ERR_INVALID_ARG unless 0 < keep_num <= keep_den,
+ * 1 <= M <= N and 1 <= k <= N'.
+ */
+int ffps_prune_sizes(int N, int M, int keep_num, int keep_den, unsigned flags, int *Nc, int *k,
+                     int *R);
+
+/*
+ * Upper bound, in bytes, of the device workspace any entry point below needs
+ * for B clouds of N points and at most M samples per cloud.  Host only.
+ * The workspace needs 256-byte alignment and no initialisation.
+ */
+int ffps_workspace_bytes(int B, int N, int M, size_t *bytes);
+
+/*
+ * Exact FPS (Sec. 3.1, Eq. 1).
+ *   d_xyz      in   [B][N][3] fp32
+ *   M          samples per cloud, 1 <= M <= N
+ *   start_idx  index of the first sample (the fixed seed point of Sec. 1), in [0, N)
+ *   variant    FFPS_VARIANT_*
+ *   d_idx      out  [B][M] int32; d_idx[b][0] = start_idx, then the picks in order
+ *   d_maxdist  out  [B][M] fp32 or NULL: squared minimum distance each pick had
+ *                   when it was chosen; entry 0 is +inf
+ *   d_ws       workspace of ws_bytes >= ffps_workspace_bytes(B, N, M)
+ */
+int ffps_exact(const float *d_xyz, int B, int N, int M, int start_idx, int variant,
+               int32_t *d_idx, float *d_maxdist, void *d_ws, size_t ws_bytes, void *stream);
+
+/*
+ * FPS-Prune (Sec. 3.2; Alg. 1, layer 1).  With (N', k, R) = ffps_prune_sizes:
+ *   candidates  the N' indices sort{ (start_idx + floor(j*N/N')) mod N : j < N' }
+ *               (an index-uniform subsample that contains start_idx);
+ *   FPS part    d_idx[b][0..k)  = exact FPS over the candidates, first sample
+ *               start_idx, ties to the lowest index, mapped to indices of the
+ *               full cloud, in FPS order;
+ *   fill part   d_idx[b][k..M)  = free[floor(j*(N-k)/R)], j < R, where free is
+ *               the ascending list of the N-k indices the FPS part did not pick
+ *               (drawn from the full cloud, not from the candidates).
+ * keep = 1/1 (p = 0) gives exactly ffps_exact.  k_out_host (may be NULL)
+ * receives k.  Other arguments as ffps_exact.
+ */
+int ffps_prune(const float *d_xyz, int B, int N, int M, int start_idx, int keep_num,
+               int keep_den, unsigned flags, int variant, int32_t *d_idx, int *k_out_host,
+               void *d_ws, size_t ws_bytes, void *stream);
+
+/*
+ * Hierarchical stage chain (Alg. 1; Sec. 3.3).
+ *   L, M_stages  host array of L sample counts, N >= M_stages[0] >= ... >= M_stages[L-1] >= 1
+ *   layer 1      ffps_prune with M = M_stages[0] (exact FPS when keep = 1/1)
+ *   FFPS_MODE_CACHED  layer l = first M_stages[l] entries of layer 1
+ *   FFPS_MODE_CHAIN   layer l = exact FPS over the points of layer l-1 taken in
+ *                     sample order, started at its first point, M_stages[l]
+ *                     picks, mapped back to indices of the full cloud
+ *   d_idx        out [B][S], S = sum of M_stages; layer l of cloud b starts at
+ *                d_idx[b*S + M_stages[0] + ... + M_stages[l-1]]
+ *   d_ws         workspace of ws_bytes >= ffps_workspace_bytes(B, N, M_stages[0])
+ */
+int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_stages,
+                       int start_idx, int keep_num, int keep_den, unsigned flags, int mode,
+                       int variant, int32_t *d_idx, void *d_ws, size_t ws_bytes, void *stream);
+
+/*
+ * Status word the kernels of the last call on this workspace left behind:
+ * synchronises `stream`, copies one int from the workspace and returns it
+ * (FFPS_OK, or FFPS_ERR_TIMEOUT when a workgroup stopped waiting for another;
+ * the outputs of that call are then undefined).
+ */
+int ffps_last_status(const void *d_ws, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHFPS_H */

@@ -1,0 +1,290 @@
+// C-ABI layer: argument validation, workspace carving and kernel dispatch.
+// Every step of the sampling path runs in the kernels of this library; the
+// host side only validates, sizes and enqueues.
+#include <hip/hip_runtime.h>
+#include <string.h>
+
+#include "../../include/flashfps.h"
+#include "fps_launch.h"
+
+namespace {
+
+using namespace ffps;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Workspace {  // byte offsets into the caller's workspace
+    size_t status, exchange, cxyz, loc, bitmap, mind, total;
+};
+
+Workspace carve(int B, int N, int M) {
+    Workspace w;
+    size_t o = 0;
+    w.status = o;   o += kAlign;
+    w.exchange = o; o += align_up(grid_exchange_bytes());
+    w.cxyz = o;     o += align_up((size_t)B * N * 3 * sizeof(float));
+    w.loc = o;      o += align_up((size_t)B * M * sizeof(int32_t));
+    w.bitmap = o;   o += align_up((size_t)B * ((N + 31) / 32) * sizeof(uint32_t));
+    w.mind = o;     o += align_up((size_t)B * N * sizeof(float));
+    w.total = o;
+    return w;
+}
+
+struct Device {
+    int ok;      // FFPS_OK or an error code
+    int num_cu;
+};
+
+// Properties of the current device (queried per call: cheap, and keeps the
+// library free of mutable global state).
+Device query_device() {
+    Device d{FFPS_ERR_LAUNCH_FAILED, 0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return d;
+    hipDeviceProp_t p;
+    if (hipGetDeviceProperties(&p, dev) != hipSuccess) return d;
+    if (strncmp(p.gcnArchName, "gfx950", 6) != 0) {
+        d.ok = FFPS_ERR_UNSUPPORTED_DEVICE;
+        return d;
+    }
+    d.ok = FFPS_OK;
+    d.num_cu = p.multiProcessorCount;
+    return d;
+}
+
+inline int hip_rc(hipError_t e) { return e == hipSuccess ? FFPS_OK : FFPS_ERR_LAUNCH_FAILED; }
+
+int check_common(const void *xyz, int B, int N, int M, int start, const void *idx, const void *ws) {
+    if (!xyz || !idx || !ws) return FFPS_ERR_INVALID_ARG;
+    if (B < 1 || N < 1 || M < 1 || M > N) return FFPS_ERR_INVALID_ARG;
+    if (start < 0 || start >= N) return FFPS_ERR_INVALID_ARG;
+    if ((long)B * N > (1L << 31) - 1) return FFPS_ERR_INVALID_ARG;
+    return FFPS_OK;
+}
+
+// `variant` carries the kernel choice in its low byte and the optional
+// picks-per-round cap above it (FFPS_VARIANT_WITH_PICKS).
+inline int variant_kind(int variant) { return variant & 0xff; }
+inline int variant_picks(int variant) {
+    int p = (variant >> 8) & 0xff;
+    return p == 0 ? kMaxPicksPerRound : p;
+}
+int check_variant(int variant) {
+    if (variant < 0 || (variant >> 16) != 0) return FFPS_ERR_INVALID_ARG;
+    int v = variant_kind(variant);
+    return (v >= FFPS_VARIANT_AUTO && v <= FFPS_VARIANT_STREAM) ? FFPS_OK : FFPS_ERR_INVALID_ARG;
+}
+
+// The status word is cleared once per call; the exchange area before every
+// grid launch (its tags restart at 1 in each launch).
+int clear_status(char *ws, const Workspace &w, hipStream_t s) {
+    return hip_rc(launch_fill_zero(ws + w.status, kAlign, s));
+}
+int clear_exchange(char *ws, const Workspace &w, hipStream_t s) {
+    return hip_rc(launch_fill_zero(ws + w.exchange, grid_exchange_bytes(), s));
+}
+
+// Kernel variant that will run for clouds of N points, or a negative error.
+int resolve_variant(int B, int N, int variant, const Device &dev) {
+    int v = variant_kind(variant);
+    if (v == FFPS_VARIANT_AUTO) {
+        if (N <= wg_capacity() && (B >= 4 || N <= 2048))
+            v = FFPS_VARIANT_WG;
+        else if (N <= grid_capacity(dev.num_cu))
+            v = FFPS_VARIANT_GRID;
+        else
+            v = FFPS_VARIANT_STREAM;
+    }
+    if (v == FFPS_VARIANT_WG && N > wg_capacity()) return FFPS_ERR_UNSUPPORTED_SIZE;
+    if (v == FFPS_VARIANT_GRID && N > grid_capacity(dev.num_cu)) return FFPS_ERR_UNSUPPORTED_SIZE;
+    if (v == FFPS_VARIANT_STREAM) return FFPS_ERR_UNSUPPORTED_SIZE;  // not built yet
+    return v;
+}
+
+// Exact FPS of B clouds [N] into idx (row stride idx_stride).  Arguments are
+// already validated.
+int run_exact(const float *xyz, int B, int N, int M, int start, int variant, int32_t *idx,
+              long idx_stride, float *md, long md_stride, char *ws, const Workspace &w,
+              const Device &dev, hipStream_t s) {
+    int v = resolve_variant(B, N, variant, dev);
+    if (v < 0) return v;
+    if (v == FFPS_VARIANT_WG)
+        return hip_rc(launch_fps_wg(xyz, B, N, M, start, idx, idx_stride, md, md_stride, s));
+    if (v == FFPS_VARIANT_GRID) {
+        for (int b = 0; b < B; ++b) {
+            int rc = clear_exchange(ws, w, s);
+            if (rc) return rc;
+            hipError_t e = launch_fps_grid(xyz + (size_t)b * N * 3, N, M, start, idx + b * idx_stride,
+                                           md ? md + b * md_stride : nullptr,
+                                           (uint64_t *)(ws + w.exchange), (int *)(ws + w.status),
+                                           dev.num_cu, variant_picks(variant), s);
+            if (e != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;
+        }
+        return FFPS_OK;
+    }
+    return FFPS_ERR_UNSUPPORTED_SIZE;
+}
+
+int run_prune(const float *xyz, int B, int N, int M, int start, int keep_num, int keep_den,
+              unsigned flags, int variant, int32_t *idx, long idx_stride, char *ws,
+              const Workspace &w, const Device &dev, hipStream_t s) {
+    int Nc, k, R;
+    int rc = ffps_prune_sizes(N, M, keep_num, keep_den, flags, &Nc, &k, &R);
+    if (rc) return rc;
+    if (Nc < N) {
+        float *cxyz = (float *)(ws + w.cxyz);
+        int32_t *loc = (int32_t *)(ws + w.loc);
+        rc = hip_rc(launch_gather_candidates(xyz, B, N, Nc, start, cxyz, s));
+        if (rc) return rc;
+        long j0 = (((long)N - start) * Nc + N - 1) / N;  // where the strided list wraps
+        if (j0 > Nc) j0 = Nc;
+        int spos = (int)((Nc - j0) % Nc);  // position of start_idx in the sorted list
+        rc = run_exact(cxyz, B, Nc, k, spos, variant, loc, k, nullptr, 0, ws, w, dev, s);
+        if (rc) return rc;
+        rc = hip_rc(launch_map_candidates(loc, k, B, N, Nc, start, k, idx, idx_stride, s));
+        if (rc) return rc;
+    } else {
+        rc = run_exact(xyz, B, N, k, start, variant, idx, idx_stride, nullptr, 0, ws, w, dev, s);
+        if (rc) return rc;
+    }
+    return hip_rc(launch_fill(B, N, k, R, idx, idx_stride, (uint32_t *)(ws + w.bitmap), s));
+}
+
+}  // namespace
+
+extern "C" {
+
+int ffps_version(void) { return 100; }
+
+const char *ffps_strerror(int code) {
+    switch (code) {
+        case FFPS_OK: return "success";
+        case FFPS_ERR_INVALID_ARG: return "invalid argument";
+        case FFPS_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case FFPS_ERR_UNSUPPORTED_DEVICE: return "device is not gfx950";
+        case FFPS_ERR_LAUNCH_FAILED: return "HIP call failed";
+        case FFPS_ERR_TIMEOUT: return "a workgroup stopped waiting for another";
+        case FFPS_ERR_UNSUPPORTED_SIZE: return "kernel variant cannot hold this cloud size";
+        default: return "unknown error code";
+    }
+}
+
+int ffps_prune_sizes(int N, int M, int keep_num, int keep_den, unsigned flags, int *Nc, int *k,
+                     int *R) {
+    if (!Nc || !k || !R) return FFPS_ERR_INVALID_ARG;
+    if (N < 1 || M < 1 || M > N) return FFPS_ERR_INVALID_ARG;
+    if (keep_num < 1 || keep_den < 1 || keep_num > keep_den) return FFPS_ERR_INVALID_ARG;
+    if (flags & ~(FFPS_FLAG_CP | FFPS_FLAG_IP)) return FFPS_ERR_INVALID_ARG;
+    long nc = (flags & FFPS_FLAG_CP) ? ((long)N * keep_num + keep_den - 1) / keep_den : N;
+    long kk = (flags & FFPS_FLAG_IP) ? ((long)M * keep_num + keep_den - 1) / keep_den : M;
+    if (kk < 1 || kk > nc) return FFPS_ERR_INVALID_ARG;
+    *Nc = (int)nc;
+    *k = (int)kk;
+    *R = M - (int)kk;
+    return FFPS_OK;
+}
+
+int ffps_workspace_bytes(int B, int N, int M, size_t *bytes) {
+    if (!bytes || B < 1 || N < 1 || M < 1 || M > N) return FFPS_ERR_INVALID_ARG;
+    if ((long)B * N > (1L << 31) - 1) return FFPS_ERR_INVALID_ARG;
+    *bytes = carve(B, N, M).total;
+    return FFPS_OK;
+}
+
+int ffps_exact(const float *d_xyz, int B, int N, int M, int start_idx, int variant, int32_t *d_idx,
+               float *d_maxdist, void *d_ws, size_t ws_bytes, void *stream) {
+    int rc = check_common(d_xyz, B, N, M, start_idx, d_idx, d_ws);
+    if (rc) return rc;
+    if ((rc = check_variant(variant))) return rc;
+    Workspace w = carve(B, N, M);
+    if (ws_bytes < w.total) return FFPS_ERR_WORKSPACE_TOO_SMALL;
+    Device dev = query_device();
+    if (dev.ok) return dev.ok;
+    if ((rc = resolve_variant(B, N, variant, dev)) < 0) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = clear_status((char *)d_ws, w, s))) return rc;
+    return run_exact(d_xyz, B, N, M, start_idx, variant, d_idx, M, d_maxdist, M, (char *)d_ws, w,
+                     dev, s);
+}
+
+int ffps_prune(const float *d_xyz, int B, int N, int M, int start_idx, int keep_num, int keep_den,
+               unsigned flags, int variant, int32_t *d_idx, int *k_out_host, void *d_ws,
+               size_t ws_bytes, void *stream) {
+    int rc = check_common(d_xyz, B, N, M, start_idx, d_idx, d_ws);
+    if (rc) return rc;
+    if ((rc = check_variant(variant))) return rc;
+    int Nc, k, R;
+    if ((rc = ffps_prune_sizes(N, M, keep_num, keep_den, flags, &Nc, &k, &R))) return rc;
+    Workspace w = carve(B, N, M);
+    if (ws_bytes < w.total) return FFPS_ERR_WORKSPACE_TOO_SMALL;
+    Device dev = query_device();
+    if (dev.ok) return dev.ok;
+    if ((rc = resolve_variant(B, Nc, variant, dev)) < 0) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = clear_status((char *)d_ws, w, s))) return rc;
+    if (k_out_host) *k_out_host = k;
+    return run_prune(d_xyz, B, N, M, start_idx, keep_num, keep_den, flags, variant, d_idx, M,
+                     (char *)d_ws, w, dev, s);
+}
+
+int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_stages, int start_idx,
+                       int keep_num, int keep_den, unsigned flags, int mode, int variant,
+                       int32_t *d_idx, void *d_ws, size_t ws_bytes, void *stream) {
+    if (!M_stages || L < 1) return FFPS_ERR_INVALID_ARG;
+    int rc = check_common(d_xyz, B, N, M_stages[0], start_idx, d_idx, d_ws);
+    if (rc) return rc;
+    if ((rc = check_variant(variant))) return rc;
+    if (mode != FFPS_MODE_CACHED && mode != FFPS_MODE_CHAIN) return FFPS_ERR_INVALID_ARG;
+    long S = M_stages[0];
+    for (int l = 1; l < L; ++l) {
+        if (M_stages[l] < 1 || M_stages[l] > M_stages[l - 1]) return FFPS_ERR_INVALID_ARG;
+        S += M_stages[l];
+    }
+    int Nc, k, R;
+    if ((rc = ffps_prune_sizes(N, M_stages[0], keep_num, keep_den, flags, &Nc, &k, &R))) return rc;
+    Workspace w = carve(B, N, M_stages[0]);
+    if (ws_bytes < w.total) return FFPS_ERR_WORKSPACE_TOO_SMALL;
+    Device dev = query_device();
+    if (dev.ok) return dev.ok;
+    if ((rc = resolve_variant(B, Nc, variant, dev)) < 0) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)d_ws;
+    if ((rc = clear_status(ws, w, s))) return rc;
+
+    rc = run_prune(d_xyz, B, N, M_stages[0], start_idx, keep_num, keep_den, flags, variant, d_idx, S,
+                   ws, w, dev, s);
+    if (rc) return rc;
+    long off = M_stages[0];
+    const int32_t *prev = d_idx;
+    for (int l = 1; l < L; ++l) {
+        int32_t *cur = d_idx + off;
+        if (mode == FFPS_MODE_CACHED) {
+            rc = hip_rc(launch_copy_prefix(d_idx, S, B, M_stages[l], cur, S, s));
+        } else {
+            float *pxyz = (float *)(ws + w.cxyz);
+            int32_t *loc = (int32_t *)(ws + w.loc);
+            rc = hip_rc(launch_gather_points(d_xyz, B, N, prev, S, M_stages[l - 1], pxyz, s));
+            if (rc) return rc;
+            rc = run_exact(pxyz, B, M_stages[l - 1], M_stages[l], 0, variant, loc, M_stages[l],
+                           nullptr, 0, ws, w, dev, s);
+            if (rc) return rc;
+            rc = hip_rc(launch_compose(prev, S, loc, M_stages[l], B, M_stages[l], cur, S, s));
+        }
+        if (rc) return rc;
+        prev = cur;
+        off += M_stages[l];
+    }
+    return FFPS_OK;
+}
+
+int ffps_last_status(const void *d_ws, void *stream) {
+    if (!d_ws) return FFPS_ERR_INVALID_ARG;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;
+    int st = 0;
+    if (hipMemcpy(&st, d_ws, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess)
+        return FFPS_ERR_LAUNCH_FAILED;
+    return st;
+}
+
+}  // extern "C"

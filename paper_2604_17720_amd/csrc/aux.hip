@@ -1,0 +1,193 @@
+// Index bookkeeping around the FPS loop: candidate pruning and the fill of
+// FPS-Prune (Alg. 1, layer 1), and the gathers / prefix copies of the stage
+// chain (Alg. 1, layers 2..L; Sec. 3.3).  All O(N) integer work.
+#include "fps_device.h"
+#include "fps_launch.h"
+
+namespace ffps {
+
+namespace {
+
+constexpr int kT = 256;
+
+inline int blocks_for(size_t n, int per_block = kT, int cap = 4096) {
+    size_t b = (n + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > (size_t)cap) b = cap;
+    return (int)b;
+}
+
+__global__ void k_fill_zero(uint32_t *p, size_t words) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < words;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0u;
+}
+
+// Position i of the ascending candidate list.  The raw list
+// raw[j] = (start + floor(j*N/Nc)) mod N wraps once, at j0; the sorted list is
+// the wrapped tail followed by the unwrapped head, i.e. raw[(i + j0) mod Nc].
+__device__ __forceinline__ int cand_at(int i, int N, int Nc, int start, int j0) {
+    long j = (long)i + j0;
+    if (j >= Nc) j -= Nc;
+    return (int)(((long)start + (j * (long)N) / Nc) % N);
+}
+
+__global__ void k_gather_candidates(const float *__restrict__ xyz, int N, int Nc, int start, int j0,
+                                    float *__restrict__ cxyz) {
+    const int b = blockIdx.y;
+    const float *src = xyz + (size_t)b * N * 3;
+    float *dst = cxyz + (size_t)b * Nc * 3;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < Nc; i += gridDim.x * blockDim.x) {
+        int c = cand_at(i, N, Nc, start, j0);
+        dst[3 * (size_t)i + 0] = src[3 * (size_t)c + 0];
+        dst[3 * (size_t)i + 1] = src[3 * (size_t)c + 1];
+        dst[3 * (size_t)i + 2] = src[3 * (size_t)c + 2];
+    }
+}
+
+__global__ void k_map_candidates(const int32_t *__restrict__ loc, long loc_stride, int N, int Nc,
+                                 int start, int j0, int k, int32_t *__restrict__ idx,
+                                 long idx_stride) {
+    const int b = blockIdx.y;
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < k; j += gridDim.x * blockDim.x)
+        idx[b * idx_stride + j] = cand_at(loc[b * loc_stride + j], N, Nc, start, j0);
+}
+
+// One workgroup per cloud: bitmap of the k FPS picks, ranks of the free
+// indices by popcount + scan, then every free index decides on its own whether
+// some j maps to its rank: fill[j] = free[floor(j*F/R)], F = N - k.  Since
+// F >= R the ranks floor(j*F/R) are distinct, and rank r is hit exactly by
+// j = ceil(r*R/F) when floor(j*F/R) == r.
+__global__ __launch_bounds__(1024) void k_fill(int N, int k, int R, int32_t *__restrict__ idx_all,
+                                               long idx_stride, uint32_t *__restrict__ bitmap_all) {
+    __shared__ int part[1024];
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int words = (N + 31) / 32;
+    uint32_t *bm = bitmap_all + (size_t)b * words;
+    int32_t *idx = idx_all + b * idx_stride;
+
+    for (int i = tid; i < words; i += 1024) bm[i] = 0u;
+    __syncthreads();
+    for (int j = tid; j < k; j += 1024) {
+        int v = idx[j];
+        atomicOr(&bm[v >> 5], 1u << (v & 31));
+    }
+    __syncthreads();
+
+    const int per = (words + 1023) / 1024;
+    const int w0 = tid * per;
+    const int w1 = min(words, w0 + per);
+    int cnt = 0;
+    for (int wd = w0; wd < w1; ++wd) {
+        uint32_t valid = (wd == words - 1 && (N & 31)) ? ((1u << (N & 31)) - 1u) : 0xffffffffu;
+        cnt += __popc(~bm[wd] & valid);
+    }
+    part[tid] = cnt;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {  // inclusive scan
+        int v = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    long r = part[tid] - cnt;  // rank of this thread's first free index
+    const long F = (long)N - k;
+    for (int wd = w0; wd < w1; ++wd) {
+        uint32_t valid = (wd == words - 1 && (N & 31)) ? ((1u << (N & 31)) - 1u) : 0xffffffffu;
+        uint32_t free_bits = ~bm[wd] & valid;
+        while (free_bits) {
+            int bit = __ffs(free_bits) - 1;
+            free_bits &= free_bits - 1;
+            long j = (r * R + F - 1) / F;
+            if (j < R && (j * F) / R == r) idx[k + j] = wd * 32 + bit;
+            ++r;
+        }
+    }
+}
+
+__global__ void k_gather_points(const float *__restrict__ xyz, int N, const int32_t *__restrict__ sel,
+                                long sel_stride, int S, float *__restrict__ dst) {
+    const int b = blockIdx.y;
+    const float *src = xyz + (size_t)b * N * 3;
+    float *out = dst + (size_t)b * S * 3;
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < S; j += gridDim.x * blockDim.x) {
+        int c = sel[b * sel_stride + j];
+        out[3 * (size_t)j + 0] = src[3 * (size_t)c + 0];
+        out[3 * (size_t)j + 1] = src[3 * (size_t)c + 1];
+        out[3 * (size_t)j + 2] = src[3 * (size_t)c + 2];
+    }
+}
+
+__global__ void k_compose(const int32_t *__restrict__ prev, long prev_stride,
+                          const int32_t *__restrict__ loc, long loc_stride, int S,
+                          int32_t *__restrict__ out, long out_stride) {
+    const int b = blockIdx.y;
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < S; j += gridDim.x * blockDim.x)
+        out[b * out_stride + j] = prev[b * prev_stride + loc[b * loc_stride + j]];
+}
+
+__global__ void k_copy_prefix(const int32_t *__restrict__ src, long src_stride, int S,
+                              int32_t *__restrict__ out, long out_stride) {
+    const int b = blockIdx.y;
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < S; j += gridDim.x * blockDim.x)
+        out[b * out_stride + j] = src[b * src_stride + j];
+}
+
+inline int wrap_point(int N, int Nc, int start) {
+    // smallest j with start + floor(j*N/Nc) >= N, capped at Nc (no wrap)
+    long j0 = (((long)N - start) * Nc + N - 1) / N;
+    return (int)(j0 > Nc ? Nc : j0);
+}
+
+}  // namespace
+
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
+    size_t words = bytes / 4;
+    hipLaunchKernelGGL(k_fill_zero, dim3(blocks_for(words)), dim3(kT), 0, s, (uint32_t *)p, words);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_candidates(const float *xyz, int B, int N, int Nc, int start, float *cxyz,
+                                    hipStream_t s) {
+    hipLaunchKernelGGL(k_gather_candidates, dim3(blocks_for(Nc), B), dim3(kT), 0, s, xyz, N, Nc,
+                       start, wrap_point(N, Nc, start), cxyz);
+    return hipGetLastError();
+}
+
+hipError_t launch_map_candidates(const int32_t *loc, long loc_stride, int B, int N, int Nc,
+                                 int start, int k, int32_t *idx, long idx_stride, hipStream_t s) {
+    hipLaunchKernelGGL(k_map_candidates, dim3(blocks_for(k), B), dim3(kT), 0, s, loc, loc_stride, N,
+                       Nc, start, wrap_point(N, Nc, start), k, idx, idx_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill(int B, int N, int k, int R, int32_t *idx, long idx_stride, uint32_t *bitmap,
+                       hipStream_t s) {
+    if (R <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill, dim3(B), dim3(1024), 0, s, N, k, R, idx, idx_stride, bitmap);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_points(const float *xyz, int B, int N, const int32_t *sel, long sel_stride,
+                                int S, float *dst, hipStream_t s) {
+    hipLaunchKernelGGL(k_gather_points, dim3(blocks_for(S), B), dim3(kT), 0, s, xyz, N, sel,
+                       sel_stride, S, dst);
+    return hipGetLastError();
+}
+
+hipError_t launch_compose(const int32_t *prev, long prev_stride, const int32_t *loc, long loc_stride,
+                          int B, int S, int32_t *out, long out_stride, hipStream_t s) {
+    hipLaunchKernelGGL(k_compose, dim3(blocks_for(S), B), dim3(kT), 0, s, prev, prev_stride, loc,
+                       loc_stride, S, out, out_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_prefix(const int32_t *src, long src_stride, int B, int S, int32_t *out,
+                              long out_stride, hipStream_t s) {
+    hipLaunchKernelGGL(k_copy_prefix, dim3(blocks_for(S), B), dim3(kT), 0, s, src, src_stride, S,
+                       out, out_stride);
+    return hipGetLastError();
+}
+
+}  // namespace ffps

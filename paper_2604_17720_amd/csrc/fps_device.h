@@ -1,0 +1,99 @@
+// Device-side building blocks shared by the FPS kernels (gfx950, wave64).
+//
+// Everything that decides a pick is written so that the result does not depend
+// on the launch shape: distances use individually rounded fp32 operations (no
+// FMA), and every reduction orders candidates by (value descending, index
+// ascending), which is a total order.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#pragma clang fp contract(off)
+
+namespace ffps {
+
+constexpr int kWave = 64;
+
+// Squared distance of Eq. 1's norm: ((dx*dx) + (dy*dy)) + (dz*dz), each
+// operation rounded to nearest-even fp32, never contracted.
+__device__ __forceinline__ float sqdist(float x, float y, float z, float lx, float ly, float lz) {
+    float dx = __fsub_rn(x, lx);
+    float dy = __fsub_rn(y, ly);
+    float dz = __fsub_rn(z, lz);
+    float xx = __fmul_rn(dx, dx);
+    float yy = __fmul_rn(dy, dy);
+    float zz = __fmul_rn(dz, dz);
+    return __fadd_rn(__fadd_rn(xx, yy), zz);
+}
+
+// Distances are >= +0 (or +inf), so their IEEE bit patterns order like
+// unsigned integers; reductions run on the bits.
+__device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
+__device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
+
+// --- DPP cross-lane moves (GFX9 encodings) ----------------------------------
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
+constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143;
+
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+    // lanes whose source is out of range, or whose row is masked off, get 0:
+    // the identity of an unsigned max
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// Unsigned max over each row of 16 lanes; the result is in lanes 15, 31, 47, 63.
+__device__ __forceinline__ uint32_t row16_max_u32(uint32_t v) {
+    v = umax(v, dpp_or_zero<kDppRowShr1>(v));
+    v = umax(v, dpp_or_zero<kDppRowShr2>(v));
+    v = umax(v, dpp_or_zero<kDppRowShr4>(v));
+    v = umax(v, dpp_or_zero<kDppRowShr8>(v));
+    return v;
+}
+
+// Unsigned max over the 64 lanes of a wave, returned as a wave-uniform value.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    v = row16_max_u32(v);
+    v = umax(v, dpp_or_zero<kDppRowBcast15, 0xa>(v));
+    v = umax(v, dpp_or_zero<kDppRowBcast31, 0xc>(v));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// Lowest lane for which pred holds (pred must hold in at least one lane).
+__device__ __forceinline__ int first_lane(bool pred) {
+    return (int)__builtin_ctzll(__builtin_amdgcn_ballot_w64(pred));
+}
+
+__device__ __forceinline__ float readlane_f(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ __forceinline__ int readlane_i(int v, int lane) {
+    return __builtin_amdgcn_readlane(v, lane);
+}
+
+// Element `sel` (wave-uniform) of a register array, read from lane `lane`
+// (wave-uniform).  The switch keeps the array in registers: each case names a
+// fixed element, and `sel` being uniform makes the branches scalar.
+template <int P>
+__device__ __forceinline__ float pick_elem(const float (&a)[P], int sel, int lane) {
+    float r = 0.f;
+#pragma unroll
+    for (int j = 0; j < P; ++j)
+        if (sel == j) r = readlane_f(a[j], lane);
+    return r;
+}
+
+// --- 64-bit words exchanged between workgroups --------------------------------
+// Relaxed, device-scope, single-copy-atomic 64-bit accesses.  Each word carries
+// its own tag (upper half), so no fence is needed between words.
+__device__ __forceinline__ void store_word(uint64_t *p, uint32_t payload, uint32_t tag) {
+    __hip_atomic_store(p, ((uint64_t)tag << 32) | payload, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t load_word(const uint64_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace ffps

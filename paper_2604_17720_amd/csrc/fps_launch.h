@@ -1,0 +1,47 @@
+// Host-side launch interface between the C-ABI layer (api.hip) and the kernel
+// translation units.  Plain pointers and sizes only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ffps {
+
+// ---- fps_wg.hip: one workgroup per cloud ------------------------------------
+int wg_capacity();  // largest N the register-resident single-workgroup kernel holds
+hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, int32_t *idx,
+                         long idx_stride, float *md, long md_stride, hipStream_t s);
+
+// ---- fps_grid.hip: one cloud over the whole device --------------------------
+constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a grid launch may use
+constexpr int kRecWords = 8;         // 64-bit words per exchange record (6 used)
+constexpr int kMaxPicksPerRound = 32;
+size_t grid_exchange_bytes();        // bytes of the exchange area (two record buffers)
+long grid_capacity(int num_cu);      // largest N the register-resident grid kernel holds
+// One cloud.  `exchange` must have been cleared (all zero) on the same stream.
+hipError_t launch_fps_grid(const float *xyz, int N, int M, int start, int32_t *idx, float *md,
+                           uint64_t *exchange, int *status, int num_cu, int max_picks,
+                           hipStream_t s);
+
+// ---- aux.hip: small helper kernels -------------------------------------------
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+// cxyz[b][i] = xyz[b][cand(i)], cand = the sorted strided candidate list (see flashfps.h)
+hipError_t launch_gather_candidates(const float *xyz, int B, int N, int Nc, int start,
+                                    float *cxyz, hipStream_t s);
+// idx[b][j] = cand(loc[b][j]) for j < k
+hipError_t launch_map_candidates(const int32_t *loc, long loc_stride, int B, int N, int Nc,
+                                 int start, int k, int32_t *idx, long idx_stride, hipStream_t s);
+// idx[b][k + j] = j-th strided rank of the indices not in idx[b][0..k)
+hipError_t launch_fill(int B, int N, int k, int R, int32_t *idx, long idx_stride,
+                       uint32_t *bitmap, hipStream_t s);
+// dst[b][j] = xyz[b][sel[b][j]] for j < S
+hipError_t launch_gather_points(const float *xyz, int B, int N, const int32_t *sel,
+                                long sel_stride, int S, float *dst, hipStream_t s);
+// out[b][j] = prev[b][loc[b][j]] for j < S
+hipError_t launch_compose(const int32_t *prev, long prev_stride, const int32_t *loc,
+                          long loc_stride, int B, int S, int32_t *out, long out_stride,
+                          hipStream_t s);
+// out[b][j] = src[b][j] for j < S
+hipError_t launch_copy_prefix(const int32_t *src, long src_stride, int B, int S, int32_t *out,
+                              long out_stride, hipStream_t s);
+
+}  // namespace ffps

@@ -1,0 +1,108 @@
+"""The C-ABI library loads, exports every symbol include/flashfps.h declares,
+and its host-side logic (sizes, validation, error strings) behaves as the
+header says.  No compute call is made: this file runs without a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2604_17720_amd.binding as fb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "flashfps.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ffps_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    L = fb.lib()
+    names = _declared_symbols()
+    assert sorted(names) == sorted(fb.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_error_strings():
+    assert fb.ffps_version() >= 100
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5, -6):
+        s = fb.ffps_strerror(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert "unknown" in fb.ffps_strerror(-99)
+
+
+def test_prune_sizes_match_golden_table():
+    with open(os.path.join(ROOT, "tests", "golden", "prune_sizes.txt")) as f:
+        rows = [list(map(int, l.split())) for l in f if l.strip() and not l.startswith("#")]
+    for n, m, kn, kd, fl, nc, k, r in rows:
+        assert fb.ffps_prune_sizes(n, m, kn, kd, fl) == (nc, k, r)
+
+
+@pytest.mark.parametrize("args", [
+    (0, 1, 1, 1, 3), (10, 0, 1, 1, 3), (10, 11, 1, 1, 3), (10, 5, 0, 4, 3), (10, 5, 5, 4, 3),
+    (10, 5, 1, 0, 3), (10, 5, 1, 4, 4), (100, 50, 1, 4, 1),   # k = 50 > N' = 25
+])
+def test_prune_sizes_rejects(args):
+    with pytest.raises(fb.FlashFPSError) as e:
+        fb.ffps_prune_sizes(*args)
+    assert e.value.code == fb.FFPS_ERR_INVALID_ARG
+
+
+def test_workspace_bytes_monotone_and_validated():
+    a = fb.ffps_workspace_bytes(1, 1024, 512)
+    b = fb.ffps_workspace_bytes(1, 200000, 50000)
+    c = fb.ffps_workspace_bytes(8, 200000, 50000)
+    assert 0 < a < b < c and a % 256 == 0
+    assert b >= 200000 * 12 + 50000 * 4
+    for bad in [(0, 10, 5), (1, 0, 1), (1, 10, 0), (1, 10, 11), (1 << 16, 1 << 16, 1)]:
+        with pytest.raises(fb.FlashFPSError):
+            fb.ffps_workspace_bytes(*bad)
+
+
+def test_entry_points_validate_before_touching_the_device():
+    """Invalid calls return FFPS_ERR_INVALID_ARG / WORKSPACE_TOO_SMALL from host
+    checks alone (the pointers below are never dereferenced)."""
+    L = fb.lib()
+    fake = ctypes.c_void_p(0x1000)
+    big = ctypes.c_size_t(1 << 40)
+    null = ctypes.c_void_p(0)
+
+    def exact(xyz=fake, B=1, N=100, M=10, start=0, variant=0, idx=fake, ws=fake, wsb=big):
+        return L.ffps_exact(xyz, B, N, M, start, variant, idx, null, ws, wsb, null)
+
+    assert exact(xyz=null) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(idx=null) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(ws=null) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(B=0) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(N=0) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(M=0) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(M=101) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(start=-1) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(start=100) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(variant=9) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(wsb=ctypes.c_size_t(16)) == fb.FFPS_ERR_WORKSPACE_TOO_SMALL
+
+    k = ctypes.c_int(-7)
+    def prune(kn=1, kd=4, flags=3, M=10, wsb=big):
+        return L.ffps_prune(fake, 1, 100, M, 0, kn, kd, flags, 0, fake, ctypes.byref(k), fake, wsb, null)
+    assert prune(kn=0) == fb.FFPS_ERR_INVALID_ARG
+    assert prune(kn=5) == fb.FFPS_ERR_INVALID_ARG
+    assert prune(flags=8) == fb.FFPS_ERR_INVALID_ARG
+    assert prune(flags=1, M=50) == fb.FFPS_ERR_INVALID_ARG      # k = 50 > N' = 25
+    assert prune(wsb=ctypes.c_size_t(16)) == fb.FFPS_ERR_WORKSPACE_TOO_SMALL
+    assert k.value == -7                                         # untouched on failure
+
+    def stages(ms, mode=0, L_=None):
+        arr = (ctypes.c_int * len(ms))(*ms)
+        return L.ffps_cached_stages(fake, 1, 100, len(ms) if L_ is None else L_, arr, 0, 1, 1, 0,
+                                    mode, 0, fake, fake, big, null)
+    assert stages([50, 60]) == fb.FFPS_ERR_INVALID_ARG           # increasing
+    assert stages([101]) == fb.FFPS_ERR_INVALID_ARG              # M1 > N
+    assert stages([50, 0]) == fb.FFPS_ERR_INVALID_ARG
+    assert stages([50], mode=2) == fb.FFPS_ERR_INVALID_ARG
+    assert stages([50], L_=0) == fb.FFPS_ERR_INVALID_ARG

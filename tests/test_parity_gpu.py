@@ -1,0 +1,184 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by
+element, on the same seeded inputs.  Integer outputs must match bit for bit;
+the squared pick distances are fp32 values produced by the same individually
+rounded operations on both sides and must match bit for bit as well."""
+import numpy as np
+import pytest
+
+from paper_2604_17720_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+WG, GRID = 1, 2
+
+_CACHE = {}
+
+
+def _c5():
+    """The LiDAR frame takes several seconds to ray-cast; build it once."""
+    if "c5" not in _CACHE:
+        _CACHE["c5"] = inputs.make_config(5)
+    return _CACHE["c5"]
+
+
+@pytest.fixture(scope="module")
+def fb():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2604_17720_amd.binding as b
+    b.lib()
+    return b
+
+
+def _dev(x):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def _exact(fb, x, M, start=0, variant=0):
+    ws = fb.make_workspace(x.shape[0] if x.ndim == 3 else 1, x.shape[-2], M)
+    idx, md = fb.ffps_exact(_dev(x), M, start, variant, return_maxdist=True, workspace=ws)
+    assert fb.ffps_last_status(ws) == 0
+    return idx.cpu().numpy(), md.cpu().numpy()
+
+
+def _check_exact(fb, oracle, x, M, start=0, variant=0):
+    print(f"exact N={x.shape[-2]} M={M} start={start} variant={variant}", flush=True)
+    got, gmd = _exact(fb, x, M, start, variant)
+    ref, rmd = oracle.fps_exact(x, M, start, return_maxdist=True)
+    ref = ref.reshape(got.shape)
+    rmd = rmd.reshape(gmd.shape)
+    bad = np.argwhere(got != ref)
+    assert bad.size == 0, f"first mismatch at {bad[0]}: got {got[tuple(bad[0])]} want {ref[tuple(bad[0])]}"
+    assert np.array_equal(gmd.view(np.uint32), rmd.view(np.uint32))
+
+
+# ---------------------------------------------------------------- exact FPS ----
+@pytest.mark.parametrize("variant", [WG, GRID])
+def test_config1_single_cloud(fb, oracle, variant):
+    _check_exact(fb, oracle, inputs.make_config(1), 512, 0, variant)
+
+
+def test_config2_batched_shapes(fb, oracle):
+    x = inputs.make_config(2)
+    _check_exact(fb, oracle, x, 512, 0, 0)
+    _check_exact(fb, oracle, x[:3], 512, 0, GRID)
+
+
+@pytest.mark.parametrize("variant", [WG, GRID])
+def test_config3_medium_clouds(fb, oracle, variant):
+    x = inputs.make_config(3, B=2)
+    _check_exact(fb, oracle, x, 4096, 0, variant)
+
+
+@pytest.mark.parametrize("n,m,start", [
+    (1, 1, 0), (2, 2, 1), (3, 2, 0), (63, 63, 5), (64, 64, 0), (65, 65, 64), (255, 100, 3),
+    (257, 257, 0), (1000, 1000, 999), (1023, 300, 0), (1025, 300, 1024), (4097, 500, 7),
+    (5000, 1, 0), (9999, 777, 1234), (16385, 400, 0), (24576, 300, 24575),
+])
+@pytest.mark.parametrize("variant", [WG, GRID])
+def test_ragged_sizes_and_seeds(fb, oracle, variant, n, m, start):
+    x = inputs.uniform_cube(n, 31000 + n)
+    _check_exact(fb, oracle, x, m, start, variant)
+
+
+@pytest.mark.parametrize("n,m", [(30000, 500), (70001, 900), (262144, 64), (300001, 300)])
+def test_grid_multi_point_per_lane(fb, oracle, n, m):
+    x = inputs.make_config(4, N=n)[0]
+    _check_exact(fb, oracle, x, m, 17, GRID)
+
+
+@pytest.mark.parametrize("cloud", ["line", "grid2", "grid3", "dups"])
+@pytest.mark.parametrize("variant", [WG, GRID])
+def test_ties_and_duplicates(fb, oracle, variant, cloud):
+    """Integer lattices make most distances tie; duplicates force the all-zero
+    end game where index 0 is returned repeatedly."""
+    x = {"line": lambda: inputs.lattice_line(700),
+         "grid2": lambda: inputs.lattice_grid(40, 37),
+         "grid3": lambda: inputs.lattice_grid(12, 11, 10),
+         "dups": lambda: np.repeat(inputs.lattice_grid(5, 5, 4), 3, axis=0)}[cloud]()
+    n = x.shape[0]
+    _check_exact(fb, oracle, x, n, 0, variant)
+    _check_exact(fb, oracle, x, min(n, 333), n // 2, variant)
+
+
+def test_picks_per_round_do_not_change_the_result(fb, oracle):
+    x = _c5()[0][:50000]
+    ref = oracle.fps_exact(x, 1500, 0)
+    for picks in (1, 2, 7, 32):
+        print(f"picks={picks}", flush=True)
+        got, _ = _exact(fb, x, 1500, 0, fb.variant_with_picks(GRID, picks))
+        assert np.array_equal(got[0], ref)
+
+
+def test_repeated_runs_are_identical(fb):
+    x = _dev(inputs.make_config(4, N=100000))
+    ws = fb.make_workspace(1, 100000, 2000)
+    first = fb.ffps_exact(x, 2000, 0, GRID, workspace=ws).cpu().numpy()
+    for _ in range(10):
+        assert np.array_equal(fb.ffps_exact(x, 2000, 0, GRID, workspace=ws).cpu().numpy(), first)
+    assert fb.ffps_last_status(ws) == 0
+
+
+# ---------------------------------------------------------------- FPS-Prune ----
+@pytest.mark.parametrize("kn,kd", [(1, 4), (1, 2), (3, 4), (1, 1)])
+@pytest.mark.parametrize("flags", [1, 2, 3])
+@pytest.mark.parametrize("variant", [0, GRID])
+def test_prune_parity(fb, oracle, kn, kd, flags, variant):
+    x = inputs.make_config(4, N=20011)
+    for start in (0, 13579):
+        print(f"prune keep={kn}/{kd} flags={flags} start={start} variant={variant}", flush=True)
+        ws = fb.make_workspace(1, 20011, 3000)
+        got, k = fb.ffps_prune(_dev(x), 3000, kn, kd, flags, start, variant, workspace=ws)
+        assert fb.ffps_last_status(ws) == 0
+        ref = oracle.fps_prune(x[0], 3000, kn, kd, flags, start)
+        assert k == oracle.prune_sizes(20011, 3000, kn, kd, flags)[1]
+        assert np.array_equal(got.cpu().numpy()[0], ref)
+
+
+def test_prune_batched_small_clouds(fb, oracle):
+    x = inputs.make_config(2, B=5)
+    got, k = fb.ffps_prune(_dev(x), 512, 1, 2, 3, 0)
+    assert k == 256
+    assert np.array_equal(got.cpu().numpy(), oracle.fps_prune(x, 512, 1, 2, 3, 0))
+
+
+# ------------------------------------------------------------- stage chains ----
+def _stages(fb, x, ms, mode, kn=1, kd=1, flags=0, start=0, variant=0):
+    B = x.shape[0]
+    ws = fb.make_workspace(B, x.shape[1], ms[0])
+    outs = fb.ffps_cached_stages(_dev(x), ms, mode, kn, kd, flags, start, variant, workspace=ws)
+    assert fb.ffps_last_status(ws) == 0
+    return np.concatenate([o.cpu().numpy() for o in outs], axis=1)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_config2_stages(fb, oracle, mode):
+    x = inputs.make_config(2, B=6)
+    got = _stages(fb, x, (512, 128), mode)
+    assert np.array_equal(got, oracle.fps_stages(x, (512, 128), mode))
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("variant", [0, GRID])
+def test_config3_stages(fb, oracle, mode, variant):
+    x = inputs.make_config(3, B=2)
+    ms = (4096, 1024, 256, 64)
+    got = _stages(fb, x, ms, mode, variant=variant)
+    assert np.array_equal(got, oracle.fps_stages(x, ms, mode))
+
+
+def test_prefix_equivalence_on_the_gpu(fb):
+    """Sec. 3.3: without pruning the independent chain equals the cached prefixes
+    (lattice input, so ties are exercised)."""
+    x = inputs.lattice_grid(30, 29, 3)[None]
+    ms = (1500, 400, 400, 37, 1)
+    assert np.array_equal(_stages(fb, x, ms, 1), _stages(fb, x, ms, 0))
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_stages_on_pruned_first_layer(fb, oracle, mode):
+    x = _c5()[:, :40000]
+    ms = (8000, 2000, 500, 125)
+    got = _stages(fb, x, ms, mode, 1, 4, 3, 0, GRID)
+    assert np.array_equal(got, oracle.fps_stages(x, ms, mode, 1, 4, 3, 0))
