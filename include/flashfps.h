@@ -144,6 +144,14 @@ int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_sta
  */
 int ffps_last_status(const void *d_ws, void *stream);
 
+/*
+ * Number of exchange rounds the last whole-device (GRID) kernel launched on
+ * this workspace took (each round delivers one or more picks), or a negative
+ * status as ffps_last_status.  0 if no such kernel ran.  Synchronises `stream`.
+ * Diagnostic: M - 1 picks / rounds = picks per cross-workgroup exchange.
+ */
+int ffps_last_rounds(const void *d_ws, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

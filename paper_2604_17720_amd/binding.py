@@ -35,7 +35,8 @@ def variant_with_picks(variant: int, picks: int) -> int:
 
 
 EXPORTS = ["ffps_version", "ffps_strerror", "ffps_prune_sizes", "ffps_workspace_bytes",
-           "ffps_exact", "ffps_prune", "ffps_cached_stages", "ffps_last_status"]
+           "ffps_exact", "ffps_prune", "ffps_cached_stages", "ffps_last_status",
+           "ffps_last_rounds"]
 
 
 class FlashFPSError(RuntimeError):
@@ -68,6 +69,7 @@ def lib() -> ctypes.CDLL:
         L.ffps_cached_stages.argtypes = [c_vp, c_int, c_int, c_int, ip, c_int, c_int, c_int,
                                          ctypes.c_uint, c_int, c_int, c_vp, c_vp, c_sz, c_vp]
         L.ffps_last_status.argtypes = [c_vp, c_vp]
+        L.ffps_last_rounds.argtypes = [c_vp, c_vp]
         for n in EXPORTS:
             if n not in ("ffps_strerror",):
                 getattr(L, n).restype = c_int
@@ -194,3 +196,8 @@ def ffps_cached_stages(xyz, M_stages, mode=FFPS_MODE_CACHED, keep_num=1, keep_de
 def ffps_last_status(workspace, stream=None) -> int:
     torch = _torch()
     return lib().ffps_last_status(workspace.data_ptr(), _stream(torch, stream))
+
+
+def ffps_last_rounds(workspace, stream=None) -> int:
+    torch = _torch()
+    return lib().ffps_last_rounds(workspace.data_ptr(), _stream(torch, stream))

@@ -117,7 +117,7 @@ int run_exact(const float *xyz, int B, int N, int M, int start, int variant, int
             if (rc) return rc;
             hipError_t e = launch_fps_grid(xyz + (size_t)b * N * 3, N, M, start, idx + b * idx_stride,
                                            md ? md + b * md_stride : nullptr,
-                                           (uint64_t *)(ws + w.exchange), (int *)(ws + w.status),
+                                           ws + w.exchange, (int *)(ws + w.status),
                                            dev.num_cu, variant_picks(variant), s);
             if (e != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;
         }
@@ -285,6 +285,15 @@ int ffps_last_status(const void *d_ws, void *stream) {
     if (hipMemcpy(&st, d_ws, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess)
         return FFPS_ERR_LAUNCH_FAILED;
     return st;
+}
+
+int ffps_last_rounds(const void *d_ws, void *stream) {
+    if (!d_ws) return FFPS_ERR_INVALID_ARG;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;
+    int st[2] = {0, 0};
+    if (hipMemcpy(st, d_ws, sizeof(st), hipMemcpyDeviceToHost) != hipSuccess)
+        return FFPS_ERR_LAUNCH_FAILED;
+    return st[0] < 0 ? st[0] : st[1];
 }
 
 }  // extern "C"

@@ -13,13 +13,14 @@ hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, int32
 
 // ---- fps_grid.hip: one cloud over the whole device --------------------------
 constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a grid launch may use
-constexpr int kRecWords = 8;         // 64-bit words per exchange record (6 used)
 constexpr int kMaxPicksPerRound = 32;
 size_t grid_exchange_bytes();        // bytes of the exchange area (two record buffers)
 long grid_capacity(int num_cu);      // largest N the register-resident grid kernel holds
 // One cloud.  `exchange` must have been cleared (all zero) on the same stream.
+// status[0] receives an error code if a workgroup gives up, status[1] the
+// number of exchange rounds the launch took.
 hipError_t launch_fps_grid(const float *xyz, int N, int M, int start, int32_t *idx, float *md,
-                           uint64_t *exchange, int *status, int num_cu, int max_picks,
+                           void *exchange, int *status, int num_cu, int max_picks,
                            hipStream_t s);
 
 // ---- aux.hip: small helper kernels -------------------------------------------
