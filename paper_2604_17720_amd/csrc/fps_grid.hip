@@ -98,6 +98,21 @@ struct GridArgs {
     int max_picks;
 };
 
+// Phase timing of workgroup 0 (100 MHz wall clock), compiled in only for
+// profiling builds: status[8 + i] accumulates phase i, status[15] the polls.
+#ifdef FFPS_PROFILE
+#define FFPS_STAMP(i)                                        \
+    do {                                                     \
+        if (w == 0 && tid == 0) {                            \
+            uint64_t now_ = wall_clock64();                  \
+            prof_acc[i] += (uint32_t)(now_ - prof_last);     \
+            prof_last = now_;                                \
+        }                                                    \
+    } while (0)
+#else
+#define FFPS_STAMP(i) do { } while (0)
+#endif
+
 template <int NT, int P>
 __global__ __launch_bounds__(NT) void k_fps_grid(GridArgs a) {
     constexpr int NW = NT / kWave;
@@ -143,8 +158,13 @@ __global__ __launch_bounds__(NT) void k_fps_grid(GridArgs a) {
 
     int npicked = 1;
     uint32_t round = 0;
+#ifdef FFPS_PROFILE
+    uint32_t prof_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint64_t prof_last = wall_clock64();
+#endif
     while (npicked < a.M) {
         ++round;
+        FFPS_STAMP(5);
         // ---- 1. apply last round's picks, then per-lane best and bound ----
         const int cnt_prev = s_cnt;
         for (int q = 0; q < cnt_prev; ++q) {
@@ -176,7 +196,9 @@ __global__ __launch_bounds__(NT) void k_fps_grid(GridArgs a) {
             wtop[wave].z = wz;
             wtop[wave].m2 = W2;
         }
+        FFPS_STAMP(0);
         __syncthreads();  // wave tops visible; everyone is done with pk*/s_cnt
+        FFPS_STAMP(1);
 
         if (wave == 0) {
             // ---- 2a. workgroup best and bound ----
@@ -197,6 +219,7 @@ __global__ __launch_bounds__(NT) void k_fps_grid(GridArgs a) {
                 store_chunk(buf + (size_t)slot * 16, ca);
                 store_chunk(buf + kChunkBytes + (size_t)slot * 16, cb4);
             }
+            FFPS_STAMP(2);
             // ---- 2c. gather: lane L reads slots q*64+L = workgroups 4L+q ----
             u32x4 ra[kRPL], rb4[kRPL];
             bool gave_up = false;
@@ -210,12 +233,16 @@ __global__ __launch_bounds__(NT) void k_fps_grid(GridArgs a) {
                               rb4[q].w == chunk_check(rb4[q].x, rb4[q].y, rb4[q].z, round, 1);
                     all = all && (ok || lane * kRPL + q >= G);
                 }
+#ifdef FFPS_PROFILE
+                if (w == 0 && tid == 0) ++prof_acc[7];
+#endif
                 if (__builtin_amdgcn_ballot_w64(!all) == 0) break;
                 if (spin >= kSpinLimit) {
                     gave_up = true;
                     break;
                 }
             }
+            FFPS_STAMP(3);
             if (gave_up) {
                 if (lane == 0) {
                     __hip_atomic_store(a.status, -5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -346,12 +373,17 @@ __global__ __launch_bounds__(NT) void k_fps_grid(GridArgs a) {
                 }
                 if (lane == 0) s_cnt = cnt;
             }
+            FFPS_STAMP(4);
         }
         __syncthreads();  // picks of this round visible to all waves
         if (s_abort) return;
         npicked += s_cnt;
     }
     if (w == 0 && tid == 0) a.status[1] = (int)round;  // exchange rounds this launch took
+#ifdef FFPS_PROFILE
+    if (w == 0 && tid == 0)
+        for (int i = 0; i < 8; ++i) a.status[8 + i] = (int)prof_acc[i];
+#endif
 }
 
 template <int NT, int P>
