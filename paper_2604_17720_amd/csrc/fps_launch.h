@@ -13,7 +13,7 @@ hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, int32
 
 // ---- fps_grid.hip: one cloud over the whole device --------------------------
 constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a grid launch may use
-constexpr int kMaxPicksPerRound = 32;
+constexpr int kMaxPicksPerRound = 64;
 size_t grid_exchange_bytes();        // bytes of the exchange area (two record buffers)
 long grid_capacity(int num_cu);      // largest N the register-resident grid kernel holds
 // One cloud.  `exchange` must have been cleared (all zero) on the same stream.

@@ -105,7 +105,7 @@ def test_ties_and_duplicates(fb, oracle, variant, cloud):
 def test_picks_per_round_do_not_change_the_result(fb, oracle):
     x = _c5()[0][:50000]
     ref = oracle.fps_exact(x, 1500, 0)
-    for picks in (1, 2, 7, 32):
+    for picks in (1, 2, 7, 33, 64):
         print(f"picks={picks}", flush=True)
         got, _ = _exact(fb, x, 1500, 0, fb.variant_with_picks(GRID, picks))
         assert np.array_equal(got[0], ref)
