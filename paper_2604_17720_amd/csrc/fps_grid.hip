@@ -183,6 +183,8 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
     static_assert(NWK % 3 == 0 && NWK >= 3 && NWK <= 12, "worker waves come in threes");
     __shared__ WaveTop wtop[NWK];
     __shared__ __attribute__((aligned(16))) u32x4 pk[kMaxPicksPerRound];
+    __shared__ int pk_id[kMaxPicksPerRound];        // candidate number of each pick of the round
+    __shared__ uint32_t pk_val[kMaxPicksPerRound];  // and the value it was picked with
     __shared__ int fin[2];  // {batch id, picks emitted in total once that batch is complete}
     __shared__ int s_abort;
     __shared__ uint32_t cmp_v[2 * kWave];
@@ -300,7 +302,9 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
     uint32_t round = 0;
 #ifdef FFPS_PROFILE
     uint32_t prof_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint32_t prof_loop[4] = {0, 0, 0, 0};  // cycles/16 and picks inside the packed loops
     uint64_t prof_last = wall_clock64();
+    const uint64_t prof_w0 = prof_last, prof_c0 = clock64();
 #endif
     while (npicked < a.M) {
         ++round;
@@ -399,18 +403,16 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
         }
         // ---- 3. replay the greedy rule on the published candidates ----
         const uint32_t Bound = wave_max_u32(lb);
-        const int cap = min(a.max_picks, a.M - npicked);
-        // hand a pick to the workers; its owner also records it in the output
-        auto emit = [&](int c, int cid, uint32_t vbits, float ex, float ey, float ez) {
-            if (lane == 0) {
-                const int seq = npicked + c;
+        const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
+        // Hand pick number c of this round to the workers (one 16-byte LDS write) and
+        // note which candidate it was; `mine` holds in exactly one lane.
+        auto emit = [&](bool mine, int c, int cid, uint32_t vbits, float ex, float ey, float ez) {
+            if (mine) {
                 u32x4 s;
-                s.x = f2u(ex); s.y = f2u(ey); s.z = f2u(ez); s.w = (uint32_t)seq;
+                s.x = f2u(ex); s.y = f2u(ey); s.z = f2u(ez); s.w = (uint32_t)(npicked + c);
                 lds_write16(pk_off + c * 16, s);
-                if ((cid >> 1) == w) {
-                    a.idx_out[seq] = (cid & 1) ? ib : ia;
-                    if (a.md_out) a.md_out[seq] = u2f(vbits);
-                }
+                pk_id[c] = cid;
+                pk_val[c] = vbits;
             }
         };
         uint32_t bv = cv[0];
@@ -438,7 +440,19 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
                 before += __builtin_popcountll(mk & lt);
             }
         }
-        if (total >= 1 && total <= 2 * kWave) {
+        // With at most 128 live candidates whose values lie within 2^24 ulps above
+        // the bound, value and position fit one 32-bit key
+        //   key = (value_bits - bound_bits) << 7 | (127 - position),
+        // so a single wave-wide max yields the best value AND, among equal values,
+        // the lowest position (= lowest index).  Values at or below the bound
+        // saturate to 0 and end the round.
+        const bool packed = total >= 1 && total <= 2 * kWave && V - Bound < (1u << 24);
+#ifdef FFPS_PROFILE
+        if (w == 0 && tid == 0) {
+            if (packed) prof_acc[total <= kWave ? 5 : 6] += 1;
+        }
+#endif
+        if (packed) {
             int pos = before;
 #pragma unroll
             for (int q = 0; q < kCPL; ++q) {
@@ -459,17 +473,25 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
                 int id0 = h ? cmp_id[lane] : 0;
                 float x0 = h ? cmp_x[lane] : 0.f, y0 = h ? cmp_y[lane] : 0.f,
                       z0 = h ? cmp_z[lane] : 0.f;
+                const uint32_t inv = 127u - (uint32_t)lane;
+#ifdef FFPS_PROFILE
+                const uint64_t lc0 = clock64();
+#endif
                 while (true) {
-                    V = wave_max_u32(v0);
-                    if (cnt > 0 && !(V > Bound)) break;
-                    pl = first_lane(v0 == V);  // lowest lane = lowest index
+                    const uint32_t K = wave_max_u32((__builtin_elementwise_sub_sat(v0, Bound) << 7) | inv);
+                    if ((K >> 7) == 0) break;  // cannot happen for the first pick
+                    pl = 127 - (int)(K & 127u);
                     px = readlane_f(x0, pl);
                     py = readlane_f(y0, pl);
                     pz = readlane_f(z0, pl);
-                    emit(cnt, readlane_i(id0, pl), V, px, py, pz);
+                    emit(lane == pl, cnt, id0, v0, x0, y0, z0);  // the winning lane hands over its own
                     if (++cnt >= cap) break;
                     v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
                 }
+#ifdef FFPS_PROFILE
+                prof_loop[0] += (uint32_t)(clock64() - lc0);
+                prof_loop[1] += cnt;
+#endif
             } else {
                 // two candidates per lane: lane L takes positions 2L and 2L+1
                 const int p0 = 2 * lane, p1 = 2 * lane + 1;
@@ -480,25 +502,36 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
                       z0 = h0 ? cmp_z[p0] : 0.f;
                 float x1 = h1 ? cmp_x[p1] : 0.f, y1 = h1 ? cmp_y[p1] : 0.f,
                       z1 = h1 ? cmp_z[p1] : 0.f;
+                const uint32_t inv0 = 127u - (uint32_t)p0, inv1 = 127u - (uint32_t)p1;
+#ifdef FFPS_PROFILE
+                const uint64_t lc0 = clock64();
+#endif
                 while (true) {
-                    const bool second = v1 > v0;  // strict: position 2L before 2L+1
-                    const uint32_t vb2 = second ? v1 : v0;
-                    V = wave_max_u32(vb2);
-                    if (cnt > 0 && !(V > Bound)) break;
-                    pl = first_lane(vb2 == V);
-                    const bool s2 = readlane_i(second ? 1 : 0, pl) != 0;
-                    px = s2 ? readlane_f(x1, pl) : readlane_f(x0, pl);
-                    py = s2 ? readlane_f(y1, pl) : readlane_f(y0, pl);
-                    pz = s2 ? readlane_f(z1, pl) : readlane_f(z0, pl);
-                    emit(cnt, s2 ? readlane_i(id1, pl) : readlane_i(id0, pl), V, px, py, pz);
+                    const uint32_t k0 = (__builtin_elementwise_sub_sat(v0, Bound) << 7) | inv0;
+                    const uint32_t k1 = (__builtin_elementwise_sub_sat(v1, Bound) << 7) | inv1;
+                    // each lane puts forward the better of its two (keys are distinct)
+                    const bool sec = k1 > k0;
+                    const float bx = sec ? x1 : x0, by = sec ? y1 : y0, bz = sec ? z1 : z0;
+                    const uint32_t K = wave_max_u32(sec ? k1 : k0);
+                    if ((K >> 7) == 0) break;
+                    pl = (127 - (int)(K & 127u)) >> 1;
+                    px = readlane_f(bx, pl);
+                    py = readlane_f(by, pl);
+                    pz = readlane_f(bz, pl);
+                    emit(lane == pl, cnt, sec ? id1 : id0, sec ? v1 : v0, bx, by, bz);
                     if (++cnt >= cap) break;
                     v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
                     v1 = f2u(fminf(u2f(v1), sqdist(x1, y1, z1, px, py, pz)));
                 }
+#ifdef FFPS_PROFILE
+                prof_loop[2] += (uint32_t)(clock64() - lc0);
+                prof_loop[3] += cnt;
+#endif
             }
         } else {
-            // a single pick (best candidate not above the bound, or cap 1), or more
-            // than 128 live candidates: work on all eight candidates per lane
+            // a single pick (best candidate not above the bound, or cap 1), more than
+            // 128 live candidates, or values spread too far above the bound for the
+            // packed key: work on all eight candidates per lane
             while (true) {
                 if (cnt > 0) {
                     bv = cv[0];
@@ -515,11 +548,19 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
                 pl = first_lane(bv == V);
                 int pq = readlane_i(bq, pl);
                 pick_xyz<kCPL>(cx, cy, cz, pq, pl, px, py, pz);
-                emit(cnt, pl * kCPL + pq, V, px, py, pz);
+                emit(lane == 0, cnt, pl * kCPL + pq, V, px, py, pz);
                 if (++cnt >= cap) break;
 #pragma unroll
                 for (int q = 0; q < kCPL; ++q)
                     cv[q] = f2u(fminf(u2f(cv[q]), sqdist(cx[q], cy[q], cz[q], px, py, pz)));
+            }
+        }
+        // the workgroup that owns a pick records it (same wave wrote pk_id / pk_val)
+        if (lane < cnt) {
+            const int cid = pk_id[lane];
+            if ((cid >> 1) == w) {
+                a.idx_out[npicked + lane] = (cid & 1) ? ib : ia;
+                if (a.md_out) a.md_out[npicked + lane] = u2f(pk_val[lane]);
             }
         }
         npicked += cnt;
@@ -533,6 +574,9 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
         a.status[1] = (int)round;  // exchange rounds this launch took
 #ifdef FFPS_PROFILE
         for (int i = 0; i < 8; ++i) a.status[8 + i] = (int)prof_acc[i];
+        for (int i = 0; i < 4; ++i) a.status[20 + i] = (int)prof_loop[i];
+        a.status[16] = (int)(wall_clock64() - prof_w0);       // 10 ns units
+        a.status[17] = (int)((clock64() - prof_c0) >> 4);     // shader cycles / 16
 #endif
     }
 }
