@@ -7,8 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflashfps.so")
-SOURCES = ["api.hip", "fps_wg.hip", "fps_grid.hip", "aux.hip"]
-HEADERS = ["fps_device.h", "fps_launch.h"]
+SOURCES = ["api.hip", "fps_wg.hip", "fps_grid.hip", "fps_stream.hip", "aux.hip"]
+HEADERS = ["fps_device.h", "fps_launch.h", "fps_exchange.h"]
 
 # -ffp-contract=off: a fused multiply-add would change the low bits of the
 # squared distance and therefore the picks.  Packed fp32 ops are disabled.

@@ -98,7 +98,6 @@ int resolve_variant(int B, int N, int variant, const Device &dev) {
     }
     if (v == FFPS_VARIANT_WG && N > wg_capacity()) return FFPS_ERR_UNSUPPORTED_SIZE;
     if (v == FFPS_VARIANT_GRID && N > grid_capacity(dev.num_cu)) return FFPS_ERR_UNSUPPORTED_SIZE;
-    if (v == FFPS_VARIANT_STREAM) return FFPS_ERR_UNSUPPORTED_SIZE;  // not built yet
     return v;
 }
 
@@ -119,6 +118,19 @@ int run_exact(const float *xyz, int B, int N, int M, int start, int variant, int
                                            md ? md + b * md_stride : nullptr,
                                            ws + w.exchange, (int *)(ws + w.status),
                                            dev.num_cu, variant_picks(variant), s);
+            if (e != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;
+        }
+        return FFPS_OK;
+    }
+    if (v == FFPS_VARIANT_STREAM) {
+        for (int b = 0; b < B; ++b) {
+            int rc = clear_exchange(ws, w, s);
+            if (rc) return rc;
+            hipError_t e = launch_fps_stream(xyz + (size_t)b * N * 3, (float *)(ws + w.mind) + (size_t)b * N,
+                                             N, M, start, idx + b * idx_stride,
+                                             md ? md + b * md_stride : nullptr, ws + w.exchange,
+                                             (int *)(ws + w.status), dev.num_cu,
+                                             variant_picks(variant), s);
             if (e != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;
         }
         return FFPS_OK;

@@ -23,6 +23,12 @@ hipError_t launch_fps_grid(const float *xyz, int N, int M, int start, int32_t *i
                            void *exchange, int *status, int num_cu, int max_picks,
                            hipStream_t s);
 
+// ---- fps_stream.hip: one cloud over the whole device, streamed from HBM ------
+// `mind` is an [N] fp32 scratch array; `exchange` and `status` as for the grid kernel.
+hipError_t launch_fps_stream(const float *xyz, float *mind, int N, int M, int start, int32_t *idx,
+                             float *md, void *exchange, int *status, int num_cu, int max_picks,
+                             hipStream_t s);
+
 // ---- aux.hip: small helper kernels -------------------------------------------
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 // cxyz[b][i] = xyz[b][cand(i)], cand = the sorted strided candidate list (see flashfps.h)

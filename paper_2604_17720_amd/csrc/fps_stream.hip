@@ -1,0 +1,232 @@
+// k_fps_stream: exact FPS (Sec. 3.1, Eq. 1) of ONE cloud spread over all CUs,
+// points and running minimum distances streamed from HBM.
+//
+// For clouds that do not fit in registers.  G co-resident workgroups own
+// contiguous slices.  Per ROUND (fps_exchange.h) every workgroup makes ONE pass
+// over its slice: each point's coordinates (12 B) and minimum distance (4 B) are
+// read, all picks of the previous round are applied, the minimum distance is
+// written back (4 B), and the pass keeps the slice's two best points and the
+// bound on the rest.  Since a round delivers several picks, the 20 bytes per
+// point are paid once per round, not once per pick.
+//
+// Lanes take groups of four consecutive points (three 16-byte loads of
+// coordinates, one of distances), so index order is not lane order here and
+// reductions break value ties on the index explicitly.
+#include "fps_exchange.h"
+
+namespace ffps {
+
+namespace {
+
+constexpr int kStreamThreads = 1024;
+constexpr uint32_t kNoIndex = 0x7fffffffu;
+
+struct StreamArgs {
+    const float *xyz;
+    float *mind;  // [N] running minimum squared distance (workspace; written before read)
+    int N, M, start;
+    int chunk;  // points per workgroup, a multiple of 4
+    int32_t *idx_out;
+    float *md_out;
+    char *exchange;
+    int *status;
+    int max_picks;
+    int aligned16;  // xyz is 16-byte aligned
+};
+
+struct Top3 {  // two best (value, index) pairs and the third value, in (value desc, index asc) order
+    uint32_t v1, v2, v3;
+    uint32_t i1, i2;
+};
+
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return ~wave_max_u32(~v); }
+__device__ __forceinline__ uint32_t row_max_uniform(uint32_t v) {
+    return (uint32_t)readlane_i((int)row16_max_u32(v), 15);
+}
+__device__ __forceinline__ uint32_t row_min_uniform(uint32_t v) { return ~row_max_uniform(~v); }
+
+// Merge the Top3 of the participating lanes (`act`) into one; MAXF / MINF reduce
+// over those lanes and return wave-uniform values.
+template <typename MAXF, typename MINF>
+__device__ __forceinline__ Top3 merge_top3(const Top3 &t, bool act, int lane, MAXF maxf, MINF minf) {
+    Top3 r;
+    const uint32_t a1 = act ? t.v1 : 0u, a2 = act ? t.v2 : 0u, a3 = act ? t.v3 : 0u;
+    const uint32_t i1 = act ? t.i1 : kNoIndex, i2 = act ? t.i2 : kNoIndex;
+    r.v1 = maxf(a1);
+    r.i1 = minf(a1 == r.v1 ? i1 : kNoIndex);
+    const int l1 = first_lane(act && a1 == r.v1 && i1 == r.i1);
+    const uint32_t b = lane == l1 ? a2 : a1, bi = lane == l1 ? i2 : i1;
+    r.v2 = maxf(b);
+    r.i2 = minf(b == r.v2 ? bi : kNoIndex);
+    const int l2 = first_lane(act && b == r.v2 && bi == r.i2);
+    const uint32_t c = lane == l1 ? (l1 == l2 ? a3 : a2) : (lane == l2 ? a2 : a1);
+    r.v3 = maxf(c);
+    return r;
+}
+
+__global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
+    constexpr int NT = kStreamThreads, NW = NT / kWave;
+    __shared__ RoundLds L;
+    __shared__ Top3 wtop[NW];
+    __shared__ int s_cnt, s_abort;
+
+    const int G = gridDim.x;
+    const int w = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int lo = w * a.chunk;
+    const int hi = min(a.N, lo + a.chunk);
+    const uint32_t pk_off = lds_offset(L.pk);
+
+    if (tid == 0) {
+        u32x4 s;
+        s.x = f2u(a.xyz[3 * (size_t)a.start + 0]);
+        s.y = f2u(a.xyz[3 * (size_t)a.start + 1]);
+        s.z = f2u(a.xyz[3 * (size_t)a.start + 2]);
+        s.w = 0u;
+        lds_write16(pk_off, s);
+        s_cnt = 1;
+        s_abort = 0;
+        if (w == 0) {
+            a.idx_out[0] = a.start;
+            if (a.md_out) a.md_out[0] = __builtin_inff();
+        }
+    }
+    __syncthreads();
+
+    int npicked = 1;
+    uint32_t round = 0;
+    while (npicked < a.M) {
+        ++round;
+        const int cnt_prev = s_cnt;
+        const bool first_pass = round == 1;  // minimum distances start at +inf, nothing to read
+        // ---- 1. one pass over the slice ----
+        // running top three of this lane; -1 sorts below every distance
+        float t1 = -1.f, t2 = -1.f, t3 = -1.f;
+        uint32_t j1 = kNoIndex, j2 = kNoIndex;
+        auto track = [&](float v, uint32_t i) {
+            const bool g1 = v > t1, g2 = v > t2;  // strict: this lane visits indices in ascending order
+            t3 = fmaxf(t3, fminf(v, t2));
+            j2 = g1 ? j1 : (g2 ? i : j2);
+            t2 = fmaxf(t2, fminf(v, t1));
+            j1 = g1 ? i : j1;
+            t1 = fmaxf(t1, v);
+        };
+        for (int g = lo + tid * 4; g < hi; g += NT * 4) {
+            float px[4], py[4], pz[4], pm[4];
+            const bool full = g + 4 <= hi;
+            if (full && a.aligned16) {
+                const float4 *src = reinterpret_cast<const float4 *>(a.xyz + 3 * (size_t)g);
+                const float4 q0 = src[0], q1 = src[1], q2 = src[2];
+                px[0] = q0.x; py[0] = q0.y; pz[0] = q0.z;
+                px[1] = q0.w; py[1] = q1.x; pz[1] = q1.y;
+                px[2] = q1.z; py[2] = q1.w; pz[2] = q2.x;
+                px[3] = q2.y; py[3] = q2.z; pz[3] = q2.w;
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const bool ok = g + k < hi;
+                    px[k] = ok ? a.xyz[3 * (size_t)(g + k) + 0] : 0.f;
+                    py[k] = ok ? a.xyz[3 * (size_t)(g + k) + 1] : 0.f;
+                    pz[k] = ok ? a.xyz[3 * (size_t)(g + k) + 2] : 0.f;
+                }
+            }
+            if (first_pass) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) pm[k] = __builtin_inff();
+            } else if (full) {
+                const float4 mm = *reinterpret_cast<const float4 *>(a.mind + g);
+                pm[0] = mm.x; pm[1] = mm.y; pm[2] = mm.z; pm[3] = mm.w;
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) pm[k] = g + k < hi ? a.mind[g + k] : 0.f;
+            }
+            for (int q = 0; q < cnt_prev; ++q) {
+                const u32x4 s = lds_read16(pk_off + q * 16);
+                const float lx = u2f(s.x), ly = u2f(s.y), lz = u2f(s.z);
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    pm[k] = fminf(pm[k], sqdist(px[k], py[k], pz[k], lx, ly, lz));
+            }
+            if (full) {
+                *reinterpret_cast<float4 *>(a.mind + g) = make_float4(pm[0], pm[1], pm[2], pm[3]);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) track(pm[k], (uint32_t)(g + k));
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (g + k < hi) {
+                        a.mind[g + k] = pm[k];
+                        track(pm[k], (uint32_t)(g + k));
+                    }
+            }
+        }
+        // ---- 1b. wave top two + bound (value ties broken on the index) ----
+        Top3 mine;
+        mine.v1 = f2u(fmaxf(t1, 0.f)); mine.v2 = f2u(fmaxf(t2, 0.f)); mine.v3 = f2u(fmaxf(t3, 0.f));
+        mine.i1 = j1; mine.i2 = j2;
+        const Top3 wt = merge_top3(mine, true, lane, [](uint32_t v) { return wave_max_u32(v); },
+                                   [](uint32_t v) { return wave_min_u32(v); });
+        if (lane == 0) wtop[wave] = wt;
+        __syncthreads();  // wave tops visible; every wave is done with the picks in L.pk
+
+        if (wave == 0) {
+            // ---- 2a. workgroup top two + bound ----
+            const bool act = lane < NW;
+            const Top3 g3 = merge_top3(wtop[act ? lane : 0], act, lane,
+                                       [](uint32_t v) { return row_max_uniform(v); },
+                                       [](uint32_t v) { return row_min_uniform(v); });
+            // in index order; an index that does not exist (slice of one point) sorts last
+            RoundInput in;
+            const bool swap = g3.i2 < g3.i1;
+            const uint32_t ia = swap ? g3.i2 : g3.i1, ib = swap ? g3.i1 : g3.i2;
+            in.va = swap ? g3.v2 : g3.v1;
+            in.vb = swap ? g3.v1 : g3.v2;
+            in.bound = g3.v3;
+            in.ia = (int)ia; in.ib = (int)ib;
+            const bool ea = ia < (uint32_t)a.N, eb = ib < (uint32_t)a.N;
+            in.xa = ea ? a.xyz[3 * (size_t)(ea ? ia : 0) + 0] : 0.f;
+            in.ya = ea ? a.xyz[3 * (size_t)(ea ? ia : 0) + 1] : 0.f;
+            in.za = ea ? a.xyz[3 * (size_t)(ea ? ia : 0) + 2] : 0.f;
+            in.xb = eb ? a.xyz[3 * (size_t)(eb ? ib : 0) + 0] : 0.f;
+            in.yb = eb ? a.xyz[3 * (size_t)(eb ? ib : 0) + 1] : 0.f;
+            in.zb = eb ? a.xyz[3 * (size_t)(eb ? ib : 0) + 2] : 0.f;
+            const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
+            const int cnt = exchange_round(L, a.exchange, G, w, lane, round, in, npicked, cap,
+                                           a.idx_out, a.md_out, a.status, nullptr);
+            if (lane == 0) {
+                s_cnt = cnt < 0 ? 0 : cnt;
+                if (cnt < 0) s_abort = 1;
+            }
+        }
+        __syncthreads();  // picks of this round visible to all waves
+        if (s_abort) return;
+        npicked += s_cnt;
+    }
+    if (w == 0 && tid == 0) a.status[1] = (int)round;
+}
+
+}  // namespace
+
+hipError_t launch_fps_stream(const float *xyz, float *mind, int N, int M, int start, int32_t *idx,
+                             float *md, void *exchange, int *status, int num_cu, int max_picks,
+                             hipStream_t s) {
+    int maxG = num_cu < kMaxGridWG ? num_cu : kMaxGridWG;
+    // a workgroup pass covers 4096 points per step; do not spread thinner than that
+    int G = (N + 4095) / 4096;
+    if (G > maxG) G = maxG;
+    if (G < 1) G = 1;
+    StreamArgs a;
+    a.xyz = xyz; a.mind = mind; a.N = N; a.M = M; a.start = start;
+    a.chunk = ((N + G - 1) / G + 3) / 4 * 4;
+    a.idx_out = idx; a.md_out = md;
+    a.exchange = (char *)exchange; a.status = status;
+    a.max_picks = max_picks < 1 ? 1 : (max_picks > kMaxPicksPerRound ? kMaxPicksPerRound : max_picks);
+    a.aligned16 = ((uintptr_t)xyz & 15) == 0;
+    void *params[] = {&a};
+    return hipLaunchCooperativeKernel((const void *)k_fps_stream, dim3(G), dim3(kStreamThreads),
+                                      params, 0, s);
+}
+
+}  // namespace ffps
