@@ -23,6 +23,10 @@ N, STAGES = 200000, (50000, 12500, 3125, 781)
 KEEP = (1, 4)
 BYTES_PER_UPDATE = 20          # xyz 12 B + min-distance read 4 B + write 4 B
 HBM_PEAK_GBS = 8000.0
+# HBM bytes one launch of the dominant kernel really moves, from the hardware
+# counters in profiles/k_fps_grid_config4_hbm_counters.md (FETCH_SIZE x 2.000 +
+# WRITE_SIZE x 1.000, calibrated on a 256 MiB copy): exchange records only.
+MEASURED_TRAFFIC_BYTES = 2.000 * 226589.75 * 1024 + 1.000 * 25459.10 * 1024
 
 
 def updates_of_chain(sizes):
@@ -35,8 +39,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-picks", type=int, default=16000,
+    ap.add_argument("--cpu-picks", type=int, default=50000,
                     help="picks of the oracle's bounded sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device copy (reference for hardware byte counters)")
+    ap.add_argument("--no-stream-probe", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -82,6 +89,8 @@ def main():
         step()
     torch.cuda.synchronize()
     assert fb.ffps_last_status(ws) == 0
+    fb.ffps_exact(x, M1, 0, workspace=ws, out=out_exact)
+    rounds_exact = fb.ffps_last_rounds(ws)
 
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -97,6 +106,13 @@ def main():
     ms_cached = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
     ms_chain = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
     achieved = upd_exact * BYTES_PER_UPDATE / (ms_exact * 1e-3) / 1e9
+
+    if args.calibrate_copy:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                  # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     result = {
         "metric": "point_distance_updates_per_s",
@@ -118,17 +134,65 @@ def main():
         "exact_fps_ms": ms_exact,
         "exact_updates_per_s": upd_exact / (ms_exact * 1e-3),
         "us_per_pick_exact": ms_exact * 1e3 / (M1 - 1),
+        "exchange_rounds_exact": rounds_exact,
+        "picks_per_round_exact": (M1 - 1) / max(rounds_exact, 1),
         "flashfps_prune_cache_ms": ms_cached,
         "pruned_chain_ms": ms_chain,
         "speedup_prune_cache_vs_exact_layer1": ms_exact / ms_cached,
         "updates_per_step": upd_step,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "k_fps_grid<256,4> (exact FPS, N=200000, M=50000)",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "kernel": "k_fps_grid<3,5> (exact FPS, N=200000, M=50000)",
                      "algorithmic_bytes_per_launch": upd_exact * BYTES_PER_UPDATE,
                      "note": "points and min-distances stay in registers, so achieved is the "
                              "HBM-equivalent rate of a streaming loop, not bytes moved"},
     }
+
+    # One plain grid barrier in the same launch shape, and one exchange round that
+    # delivers a single pick: the per-pick latency of the multi-pick kernel is
+    # quoted against both.
+    result["grid_barrier_us"] = fb.ffps_barrier_probe(20000, workspace=ws)
+    m_one = 4001
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    one = fb.variant_with_picks(fb.FFPS_VARIANT_GRID, 1)
+    fb.ffps_exact(x, m_one, 0, one, workspace=ws)
+    e0.record()
+    fb.ffps_exact(x, m_one, 0, one, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    result["us_per_round_one_pick"] = e0.elapsed_time(e1) * 1e3 / (m_one - 1)
+    result["us_per_pick_over_grid_barrier"] = result["us_per_pick_exact"] / result["grid_barrier_us"]
+
+    if not args.no_stream_probe:
+        # Supplementary probe OUTSIDE the five configurations: a cloud too large for
+        # on-chip residency (32 Mi uniform points), 64 picks, streamed from HBM.
+        # One pick per pass shows the bandwidth the pass itself reaches.
+        n_big, m_big = 1 << 25, 65
+        g = torch.Generator(device="cuda")
+        g.manual_seed(4242)
+        xb = torch.rand((1, n_big, 3), generator=g, device="cuda", dtype=torch.float32)
+        wsb = fb.make_workspace(1, n_big, m_big)
+        ob = torch.empty((1, m_big), dtype=torch.int32, device="cuda")
+        probe = {"workload": f"supplementary: N={n_big} uniform points, M={m_big}, "
+                             "FFPS_VARIANT_STREAM", "bytes_per_pass": BYTES_PER_UPDATE * n_big}
+        for name, picks in (("one_pick_per_pass", 1), ("default", 0)):
+            var = fb.variant_with_picks(fb.FFPS_VARIANT_STREAM, picks)
+            fb.ffps_exact(xb, m_big, 0, var, workspace=wsb, out=ob)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fb.ffps_exact(xb, m_big, 0, var, workspace=wsb, out=ob)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            passes = fb.ffps_last_rounds(wsb)
+            probe[name] = {
+                "ms": ms, "passes": passes,
+                "hbm_gbs_moved": BYTES_PER_UPDATE * n_big * passes / (ms * 1e-3) / 1e9,
+                "hbm_gbs_algorithmic": BYTES_PER_UPDATE * n_big * (m_big - 1) / (ms * 1e-3) / 1e9,
+            }
+        probe["frac_of_peak_moved"] = probe["one_pick_per_pass"]["hbm_gbs_moved"] / HBM_PEAK_GBS
+        result["stream_probe"] = probe
+        del xb, wsb, ob
 
     if not args.no_cpu_baseline:
         import oracle

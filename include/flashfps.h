@@ -152,6 +152,16 @@ int ffps_last_status(const void *d_ws, void *stream);
  */
 int ffps_last_rounds(const void *d_ws, void *stream);
 
+/*
+ * Reference measurement for the multi-workgroup kernels: runs `iters`
+ * (1 .. 2^20) plain grid barriers (one device-scope atomic arrive plus a spin
+ * on the counter each) over one workgroup per CU, the launch shape of the GRID
+ * and STREAM variants, and stores the mean time of one barrier in
+ * microseconds to *us_per_barrier (host).  Synchronises `stream`.  d_ws as for
+ * the other calls (ffps_workspace_bytes(1, 1, 1) suffices).
+ */
+int ffps_barrier_probe(int iters, void *d_ws, size_t ws_bytes, void *stream, float *us_per_barrier);
+
 #ifdef __cplusplus
 }
 #endif

@@ -36,7 +36,7 @@ def variant_with_picks(variant: int, picks: int) -> int:
 
 EXPORTS = ["ffps_version", "ffps_strerror", "ffps_prune_sizes", "ffps_workspace_bytes",
            "ffps_exact", "ffps_prune", "ffps_cached_stages", "ffps_last_status",
-           "ffps_last_rounds"]
+           "ffps_last_rounds", "ffps_barrier_probe"]
 
 
 class FlashFPSError(RuntimeError):
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
                                          ctypes.c_uint, c_int, c_int, c_vp, c_vp, c_sz, c_vp]
         L.ffps_last_status.argtypes = [c_vp, c_vp]
         L.ffps_last_rounds.argtypes = [c_vp, c_vp]
+        L.ffps_barrier_probe.argtypes = [c_int, c_vp, c_sz, c_vp, ctypes.POINTER(ctypes.c_float)]
         for n in EXPORTS:
             if n not in ("ffps_strerror",):
                 getattr(L, n).restype = c_int
@@ -201,3 +202,15 @@ def ffps_last_status(workspace, stream=None) -> int:
 def ffps_last_rounds(workspace, stream=None) -> int:
     torch = _torch()
     return lib().ffps_last_rounds(workspace.data_ptr(), _stream(torch, stream))
+
+
+def ffps_barrier_probe(iters, workspace=None, stream=None) -> float:
+    """Mean time of one plain grid barrier (microseconds) in the GRID launch shape."""
+    torch = _torch()
+    ws = make_workspace(1, 1, 1) if workspace is None else workspace
+    out = ctypes.c_float()
+    rc = lib().ffps_barrier_probe(iters, ws.data_ptr(), ws.numel(), _stream(torch, stream),
+                                  ctypes.byref(out))
+    if rc:
+        raise FlashFPSError(rc, "ffps_barrier_probe")
+    return out.value

@@ -299,6 +299,38 @@ int ffps_last_status(const void *d_ws, void *stream) {
     return st;
 }
 
+int ffps_barrier_probe(int iters, void *d_ws, size_t ws_bytes, void *stream, float *us_per_barrier) {
+    if (!d_ws || !us_per_barrier || iters < 1 || iters > (1 << 20)) return FFPS_ERR_INVALID_ARG;
+    Workspace w = carve(1, 1, 1);
+    if (ws_bytes < w.total) return FFPS_ERR_WORKSPACE_TOO_SMALL;
+    Device dev = query_device();
+    if (dev.ok) return dev.ok;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)d_ws;
+    int rc = clear_status(ws, w, s);
+    if (rc) return rc;
+    if ((rc = clear_exchange(ws, w, s))) return rc;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+        return FFPS_ERR_LAUNCH_FAILED;
+    int G = dev.num_cu < kMaxGridWG ? dev.num_cu : kMaxGridWG;
+    hipEventRecord(e0, s);
+    hipError_t e = launch_barrier_probe((unsigned *)(ws + w.exchange), (int *)(ws + w.status), G, iters, s);
+    hipEventRecord(e1, s);
+    float ms = 0.f;
+    if (e != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+        rc = FFPS_ERR_LAUNCH_FAILED;
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (rc) return rc;
+    *us_per_barrier = ms * 1000.f / (float)iters;
+    int st = 0;
+    if (hipMemcpy(&st, ws + w.status, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess)
+        return FFPS_ERR_LAUNCH_FAILED;
+    return st;
+}
+
 int ffps_last_rounds(const void *d_ws, void *stream) {
     if (!d_ws) return FFPS_ERR_INVALID_ARG;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;

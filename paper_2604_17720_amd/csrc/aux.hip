@@ -134,6 +134,27 @@ __global__ void k_copy_prefix(const int32_t *__restrict__ src, long src_stride, 
         out[b * out_stride + j] = src[b * src_stride + j];
 }
 
+// Reference point for the multi-workgroup kernels: `iters` plain grid barriers
+// (one device-scope atomic arrive + a bounded spin on the counter per barrier).
+__global__ __launch_bounds__(256) void k_barrier_probe(unsigned *counter, int iters, int *status) {
+    const unsigned G = gridDim.x;
+    for (int it = 1; it <= iters; ++it) {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            int spin = 0;
+            while (__hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < G * (unsigned)it) {
+                if (++spin > (1 << 22)) {
+                    __hip_atomic_store(status, -5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+            }
+        }
+        __syncthreads();
+        if (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    }
+}
+
 inline int wrap_point(int N, int Nc, int start) {
     // smallest j with start + floor(j*N/Nc) >= N, capped at Nc (no wrap)
     long j0 = (((long)N - start) * Nc + N - 1) / N;
@@ -141,6 +162,12 @@ inline int wrap_point(int N, int Nc, int start) {
 }
 
 }  // namespace
+
+hipError_t launch_barrier_probe(unsigned *counter, int *status, int num_wg, int iters, hipStream_t s) {
+    void *params[] = {&counter, &iters, &status};
+    return hipLaunchCooperativeKernel((const void *)k_barrier_probe, dim3(num_wg), dim3(256), params,
+                                      0, s);
+}
 
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
     size_t words = bytes / 4;

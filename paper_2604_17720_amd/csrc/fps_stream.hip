@@ -113,54 +113,72 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
             j1 = g1 ? i : j1;
             t1 = fmaxf(t1, v);
         };
-        for (int g = lo + tid * 4; g < hi; g += NT * 4) {
+        // Two groups of four points per step: all eight 16-byte loads are issued
+        // before either group is worked on, which doubles the bytes in flight.
+        struct Group {
             float px[4], py[4], pz[4], pm[4];
+        };
+        auto load = [&](Group &gp, int g) {
             const bool full = g + 4 <= hi;
             if (full && a.aligned16) {
                 const float4 *src = reinterpret_cast<const float4 *>(a.xyz + 3 * (size_t)g);
                 const float4 q0 = src[0], q1 = src[1], q2 = src[2];
-                px[0] = q0.x; py[0] = q0.y; pz[0] = q0.z;
-                px[1] = q0.w; py[1] = q1.x; pz[1] = q1.y;
-                px[2] = q1.z; py[2] = q1.w; pz[2] = q2.x;
-                px[3] = q2.y; py[3] = q2.z; pz[3] = q2.w;
+                gp.px[0] = q0.x; gp.py[0] = q0.y; gp.pz[0] = q0.z;
+                gp.px[1] = q0.w; gp.py[1] = q1.x; gp.pz[1] = q1.y;
+                gp.px[2] = q1.z; gp.py[2] = q1.w; gp.pz[2] = q2.x;
+                gp.px[3] = q2.y; gp.py[3] = q2.z; gp.pz[3] = q2.w;
             } else {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const bool ok = g + k < hi;
-                    px[k] = ok ? a.xyz[3 * (size_t)(g + k) + 0] : 0.f;
-                    py[k] = ok ? a.xyz[3 * (size_t)(g + k) + 1] : 0.f;
-                    pz[k] = ok ? a.xyz[3 * (size_t)(g + k) + 2] : 0.f;
+                    gp.px[k] = ok ? a.xyz[3 * (size_t)(g + k) + 0] : 0.f;
+                    gp.py[k] = ok ? a.xyz[3 * (size_t)(g + k) + 1] : 0.f;
+                    gp.pz[k] = ok ? a.xyz[3 * (size_t)(g + k) + 2] : 0.f;
                 }
             }
             if (first_pass) {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) pm[k] = __builtin_inff();
+                for (int k = 0; k < 4; ++k) gp.pm[k] = __builtin_inff();
             } else if (full) {
                 const float4 mm = *reinterpret_cast<const float4 *>(a.mind + g);
-                pm[0] = mm.x; pm[1] = mm.y; pm[2] = mm.z; pm[3] = mm.w;
+                gp.pm[0] = mm.x; gp.pm[1] = mm.y; gp.pm[2] = mm.z; gp.pm[3] = mm.w;
             } else {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) pm[k] = g + k < hi ? a.mind[g + k] : 0.f;
+                for (int k = 0; k < 4; ++k) gp.pm[k] = g + k < hi ? a.mind[g + k] : 0.f;
             }
-            for (int q = 0; q < cnt_prev; ++q) {
-                const u32x4 s = lds_read16(pk_off + q * 16);
-                const float lx = u2f(s.x), ly = u2f(s.y), lz = u2f(s.z);
+        };
+        auto finish = [&](Group &gp, int g) {
+            if (g + 4 <= hi) {
+                *reinterpret_cast<float4 *>(a.mind + g) =
+                    make_float4(gp.pm[0], gp.pm[1], gp.pm[2], gp.pm[3]);
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    pm[k] = fminf(pm[k], sqdist(px[k], py[k], pz[k], lx, ly, lz));
-            }
-            if (full) {
-                *reinterpret_cast<float4 *>(a.mind + g) = make_float4(pm[0], pm[1], pm[2], pm[3]);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) track(pm[k], (uint32_t)(g + k));
+                for (int k = 0; k < 4; ++k) track(gp.pm[k], (uint32_t)(g + k));
             } else {
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
                     if (g + k < hi) {
-                        a.mind[g + k] = pm[k];
-                        track(pm[k], (uint32_t)(g + k));
+                        a.mind[g + k] = gp.pm[k];
+                        track(gp.pm[k], (uint32_t)(g + k));
                     }
             }
+        };
+        for (int g = lo + tid * 4; g < hi; g += 2 * NT * 4) {
+            const int g2 = g + NT * 4;
+            const bool two = g2 < hi;
+            Group A, B;
+            load(A, g);
+            if (two) load(B, g2);
+            for (int q = 0; q < cnt_prev; ++q) {
+                const u32x4 s = lds_read16(pk_off + q * 16);
+                const float lx = u2f(s.x), ly = u2f(s.y), lz = u2f(s.z);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    A.pm[k] = fminf(A.pm[k], sqdist(A.px[k], A.py[k], A.pz[k], lx, ly, lz));
+                    if (two) B.pm[k] = fminf(B.pm[k], sqdist(B.px[k], B.py[k], B.pz[k], lx, ly, lz));
+                }
+            }
+            finish(A, g);  // group A's indices precede group B's: ascending order is kept
+            if (two) finish(B, g2);
         }
         // ---- 1b. wave top two + bound (value ties broken on the index) ----
         Top3 mine;
