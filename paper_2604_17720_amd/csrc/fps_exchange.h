@@ -1,22 +1,24 @@
 // Cross-workgroup exchange and candidate replay shared by the multi-workgroup
 // FPS kernels (register-resident and HBM-streaming).
 //
-// Once per ROUND every workgroup contributes its two best points (listed in
-// index order) and an upper bound on all its other points.  One wave per
-// workgroup publishes them as three 16-byte chunks, each closed by a checksum
-// that also encodes the round, gathers the chunks of all G workgroups with
-// coalesced device-scope loads (the only cross-workgroup step: no counters, no
-// fences, no separate barrier), and replays the greedy rule of Eq. 1 on the 2G
-// published candidates: the best candidate is the next pick as long as its
-// value is strictly above B = max of all bounds, because no unpublished point
-// can then reach it; picking it lowers the other candidates' values by the same
-// distance rule, and the replay continues until the test fails.  The first pick
-// of a round never needs the test: the global best point is the best of its own
-// slice, hence published.  Every workgroup replays the same arithmetic on the
-// same records, so all agree on the picks without further communication.
+// Once per ROUND every workgroup contributes its two best points and an upper
+// bound on all its other points (its third-best value).  One wave per workgroup
+// publishes them as four 16-byte chunks, each closed by a checksum that also
+// encodes the round, gathers the chunks of all G workgroups with coalesced
+// device-scope loads (the only cross-workgroup step: no counters, no fences, no
+// separate barrier), and replays the greedy rule of Eq. 1 on the 2G published
+// candidates: the best candidate is the next pick as long as its value is
+// strictly above B = max of all bounds, because no unpublished point can then
+// reach it; picking it lowers the other candidates' values by the same distance
+// rule, and the replay continues until the test fails.  The first pick of a
+// round never needs the test: the global best point (largest value, lowest
+// index among equals) is the best of its own workgroup, hence published.
+// Every workgroup replays the same arithmetic on the same records, so all agree
+// on the picks without further communication.
 //
-// Ties.  Slices are in index order and a workgroup lists its two candidates in
-// index order, so "lowest position among equal values" is "lowest index".
+// "Best" always means largest value, then lowest point index.  Points may be
+// assigned to workgroups in any way; candidates carry their indices, and equal
+// values are detected and resolved on the index wherever they can occur.
 #pragma once
 #include "fps_device.h"
 #include "fps_launch.h"
@@ -26,16 +28,18 @@ namespace ffps {
 constexpr int kRPL = kMaxGridWG / kWave;  // workgroup records per lane of the gathering wave
 constexpr int kCPL = 2 * kRPL;            // candidates per lane before compaction
 constexpr int kSpinLimit = 1 << 19;
+constexpr uint32_t kNoIndex = 0x7fffffffu;  // index of a candidate that does not exist
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Exchange area: two buffers (round parity); each holds three chunk arrays
+// Exchange area: two buffers (round parity); each holds four chunk arrays
 // (A: {v_a, v_b, bound, check}, B: {x_a, y_a, z_a, check}, C: {x_b, y_b, z_b,
-// check}) of 256 slots x 16 bytes.  Workgroup w uses slot (w & 3) * 64 + (w >> 2),
-// so that a wave reading slot q*64 + lane with one 16-byte load per lane touches
-// one contiguous KiB, while lane L still ends up with workgroups 4L .. 4L+3.
+// check}, D: {i_a, i_b, 0, check}) of 256 slots x 16 bytes.  Workgroup w uses
+// slot (w & 3) * 64 + (w >> 2), so that a wave reading slot q*64 + lane with one
+// 16-byte load per lane touches one contiguous KiB.
+constexpr int kChunks = 4;
 constexpr size_t kChunkBytes = (size_t)kMaxGridWG * 16;
-constexpr size_t kBufBytes = 3 * kChunkBytes;
+constexpr size_t kBufBytes = kChunks * kChunkBytes;
 __device__ __forceinline__ int slot_of(int w) { return (w & 3) * kWave + (w >> 2); }
 
 // A chunk is valid for a round when its last word equals this value.  Memory
@@ -47,6 +51,9 @@ __device__ __forceinline__ uint32_t chunk_check(uint32_t a, uint32_t b, uint32_t
     uint32_t m = a ^ ((b << 11) | (b >> 21)) ^ ((c << 22) | (c >> 10));
     return m ^ (round * 0x9E3779B1u + which * 0x85EBCA6Bu);
 }
+__device__ __forceinline__ bool chunk_ok(const u32x4 &c, uint32_t round, uint32_t which) {
+    return c.w == chunk_check(c.x, c.y, c.z, round, which);
+}
 
 // Device-scope (all XCDs) 16-byte store and loads.  The compiler offers atomics
 // up to 8 bytes only, so these are spelled out; sc1 is the device-scope cache
@@ -54,29 +61,34 @@ __device__ __forceinline__ uint32_t chunk_check(uint32_t a, uint32_t b, uint32_t
 __device__ __forceinline__ void store_chunk(void *p, u32x4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
-// ra/rb/rc[q] = 16 bytes at pa/pb/pc + q * 1024, q < 4: all twelve loads are
-// issued before the single wait, so a poll costs one round trip.
-__device__ __forceinline__ void load_chunks3(const void *pa, const void *pb, const void *pc,
-                                             u32x4 (&ra)[kRPL], u32x4 (&rb)[kRPL],
-                                             u32x4 (&rc)[kRPL]) {
+// r*[q] = 16 bytes at p* + q * 1024, q < 4: all sixteen loads are issued before
+// the single wait, so a poll costs one round trip.
+__device__ __forceinline__ void load_chunks4(const void *pa, const void *pb, const void *pc,
+                                             const void *pd, u32x4 (&ra)[kRPL], u32x4 (&rb)[kRPL],
+                                             u32x4 (&rc)[kRPL], u32x4 (&rd)[kRPL]) {
     static_assert(kRPL == 4, "four slots per lane");
     asm volatile(
-        "global_load_dwordx4 %0, %12, off sc1\n\t"
-        "global_load_dwordx4 %1, %12, off offset:1024 sc1\n\t"
-        "global_load_dwordx4 %2, %12, off offset:2048 sc1\n\t"
-        "global_load_dwordx4 %3, %12, off offset:3072 sc1\n\t"
-        "global_load_dwordx4 %4, %13, off sc1\n\t"
-        "global_load_dwordx4 %5, %13, off offset:1024 sc1\n\t"
-        "global_load_dwordx4 %6, %13, off offset:2048 sc1\n\t"
-        "global_load_dwordx4 %7, %13, off offset:3072 sc1\n\t"
-        "global_load_dwordx4 %8, %14, off sc1\n\t"
-        "global_load_dwordx4 %9, %14, off offset:1024 sc1\n\t"
-        "global_load_dwordx4 %10, %14, off offset:2048 sc1\n\t"
-        "global_load_dwordx4 %11, %14, off offset:3072 sc1\n\t"
+        "global_load_dwordx4 %0, %16, off sc1\n\t"
+        "global_load_dwordx4 %1, %16, off offset:1024 sc1\n\t"
+        "global_load_dwordx4 %2, %16, off offset:2048 sc1\n\t"
+        "global_load_dwordx4 %3, %16, off offset:3072 sc1\n\t"
+        "global_load_dwordx4 %4, %17, off sc1\n\t"
+        "global_load_dwordx4 %5, %17, off offset:1024 sc1\n\t"
+        "global_load_dwordx4 %6, %17, off offset:2048 sc1\n\t"
+        "global_load_dwordx4 %7, %17, off offset:3072 sc1\n\t"
+        "global_load_dwordx4 %8, %18, off sc1\n\t"
+        "global_load_dwordx4 %9, %18, off offset:1024 sc1\n\t"
+        "global_load_dwordx4 %10, %18, off offset:2048 sc1\n\t"
+        "global_load_dwordx4 %11, %18, off offset:3072 sc1\n\t"
+        "global_load_dwordx4 %12, %19, off sc1\n\t"
+        "global_load_dwordx4 %13, %19, off offset:1024 sc1\n\t"
+        "global_load_dwordx4 %14, %19, off offset:2048 sc1\n\t"
+        "global_load_dwordx4 %15, %19, off offset:3072 sc1\n\t"
         "s_waitcnt vmcnt(0)"
         : "=&v"(ra[0]), "=&v"(ra[1]), "=&v"(ra[2]), "=&v"(ra[3]), "=&v"(rb[0]), "=&v"(rb[1]),
-          "=&v"(rb[2]), "=&v"(rb[3]), "=&v"(rc[0]), "=&v"(rc[1]), "=&v"(rc[2]), "=&v"(rc[3])
-        : "v"(pa), "v"(pb), "v"(pc)
+          "=&v"(rb[2]), "=&v"(rb[3]), "=&v"(rc[0]), "=&v"(rc[1]), "=&v"(rc[2]), "=&v"(rc[3]),
+          "=&v"(rd[0]), "=&v"(rd[1]), "=&v"(rd[2]), "=&v"(rd[3])
+        : "v"(pa), "v"(pb), "v"(pc), "v"(pd)
         : "memory");
 }
 
@@ -109,22 +121,70 @@ __device__ __forceinline__ void pick_xyz(const float (&x)[P], const float (&y)[P
     }
 }
 
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return ~wave_max_u32(~v); }
+// Reductions over lanes 0..15 only (other lanes must pass the identity), wave-uniform.
+__device__ __forceinline__ uint32_t row_max_uniform(uint32_t v) {
+    return (uint32_t)readlane_i((int)row16_max_u32(v), 15);
+}
+__device__ __forceinline__ uint32_t row_min_uniform(uint32_t v) { return ~row_max_uniform(~v); }
 
-// What a workgroup contributes to a round: candidates a, b in index order
-// (ia < ib) with their current values, and the bound on its other points.
+// Lane that holds the best of the pairs (value v, index i): largest value, then
+// lowest index.  `vmax` is the (uniform) largest value; the index reduction is
+// only paid when several lanes hold it.
+template <typename MINF>
+__device__ __forceinline__ int best_lane(uint32_t v, uint32_t i, uint32_t vmax, MINF minf) {
+    const uint64_t tied = __builtin_amdgcn_ballot_w64(v == vmax);
+    if (__builtin_popcountll(tied) == 1) return (int)__builtin_ctzll(tied);
+    const uint32_t imin = minf(v == vmax ? i : 0xffffffffu);
+    return first_lane(v == vmax && i == imin);
+}
+
+// Two best (value, index) pairs and the third value of a set, in (value
+// descending, index ascending) order.
+struct Top3 {
+    uint32_t v1, v2, v3;
+    uint32_t i1, i2;
+};
+
+// Merge the Top3 of the participating lanes (`act`) into one.  l1, l2 receive
+// the lanes that supplied the first and second entry, s2 whether the second
+// entry was lane l2's second (l1 == l2) rather than its first.  MAXF / MINF
+// reduce over the participating lanes and return wave-uniform values.
+template <typename MAXF, typename MINF>
+__device__ __forceinline__ Top3 merge_top3(const Top3 &t, bool act, int lane, MAXF maxf, MINF minf,
+                                           int &l1, int &l2, bool &s2) {
+    Top3 r;
+    const uint32_t a1 = act ? t.v1 : 0u, a2 = act ? t.v2 : 0u, a3 = act ? t.v3 : 0u;
+    const uint32_t i1 = act ? t.i1 : 0xffffffffu, i2 = act ? t.i2 : 0xffffffffu;
+    r.v1 = maxf(a1);
+    l1 = best_lane(a1, i1, r.v1, minf);
+    r.i1 = (uint32_t)readlane_i((int)i1, l1);
+    const uint32_t b = lane == l1 ? a2 : a1, bi = lane == l1 ? i2 : i1;
+    r.v2 = maxf(b);
+    l2 = best_lane(b, bi, r.v2, minf);
+    r.i2 = (uint32_t)readlane_i((int)bi, l2);
+    s2 = l1 == l2;
+    const uint32_t c = lane == l1 ? (s2 ? a3 : a2) : (lane == l2 ? a2 : a1);
+    r.v3 = maxf(c);
+    return r;
+}
+
+// What a workgroup contributes to a round: its two best points (any order)
+// with their current values and indices, and the bound on its other points.
+// A candidate that does not exist has value 0 and index kNoIndex.
 struct RoundInput {
     uint32_t va, vb, bound;
     float xa, ya, za, xb, yb, zb;
-    int ia, ib;
+    uint32_t ia, ib;
 };
 
 // LDS used by the wave that runs exchange_round.
 struct RoundLds {
     __attribute__((aligned(16))) u32x4 pk[kMaxPicksPerRound];  // picks of the round: {x, y, z, seq}
-    int pk_id[kMaxPicksPerRound];        // candidate number of each pick of the round
+    uint32_t pk_idx[kMaxPicksPerRound];  // index of each pick of the round
     uint32_t pk_val[kMaxPicksPerRound];  // and the value it was picked with
     uint32_t cmp_v[2 * kWave];           // compacted live candidates
-    int cmp_id[2 * kWave];
+    uint32_t cmp_i[2 * kWave];
     float cmp_x[2 * kWave], cmp_y[2 * kWave], cmp_z[2 * kWave];
 };
 
@@ -135,13 +195,13 @@ struct RoundProf {
     uint64_t last;
 };
 #ifdef FFPS_PROFILE
-#define FFPS_STAMP(P, i)                                        \
-    do {                                                        \
-        if ((P) != nullptr) {                                   \
-            uint64_t now_ = wall_clock64();                     \
-            (P)->acc[i] += (uint32_t)(now_ - (P)->last);        \
-            (P)->last = now_;                                   \
-        }                                                       \
+#define FFPS_STAMP(P, i)                                 \
+    do {                                                 \
+        if ((P) != nullptr) {                            \
+            uint64_t now_ = wall_clock64();              \
+            (P)->acc[i] += (uint32_t)(now_ - (P)->last); \
+            (P)->last = now_;                            \
+        }                                                \
     } while (0)
 #else
 #define FFPS_STAMP(P, i) \
@@ -152,50 +212,44 @@ struct RoundProf {
 // One round, run by ONE full wave of workgroup w.  Publishes `in`, gathers all
 // G records, replays, writes each pick as {x, y, z, npicked + c} to L.pk[c]
 // (16-byte LDS writes, in pick order, so other waves may consume them while
-// the replay is still running) and records the picks this workgroup owns in
-// idx_out / md_out.  Returns the number of picks of the round (1 .. cap), or -1
-// after setting *status when another workgroup's record never arrived.
+// the replay is still running); workgroup 0 records the picks in idx_out /
+// md_out.  Returns the number of picks of the round (1 .. cap), or -1 after
+// setting *status when another workgroup's record never arrived.
 __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G, int w, int lane,
                                               uint32_t round, const RoundInput &in, int npicked,
                                               int cap, int32_t *idx_out, float *md_out, int *status,
                                               RoundProf *prof) {
     const uint32_t pk_off = lds_offset(L.pk);
-    uint32_t *cmp_v = L.cmp_v;
-    int *cmp_id = L.cmp_id;
-    float *cmp_x = L.cmp_x, *cmp_y = L.cmp_y, *cmp_z = L.cmp_z;
-    int *pk_id = L.pk_id;
-    uint32_t *pk_val = L.pk_val;
-    const uint32_t va = in.va, vb = in.vb, G3 = in.bound;
-    const float xa = in.xa, ya = in.ya, za = in.za, xb = in.xb, yb = in.yb, zb = in.zb;
-    const int ia = in.ia, ib = in.ib;
-    // ---- 2b. publish ----
+    // ---- publish ----
     char *buf = exchange + (size_t)(round & 1) * kBufBytes;
     if (lane == 0) {
-        u32x4 ca, cb4, cc4;
-        ca.x = va; ca.y = vb; ca.z = G3;
-        ca.w = chunk_check(ca.x, ca.y, ca.z, round, 0);
-        cb4.x = f2u(xa); cb4.y = f2u(ya); cb4.z = f2u(za);
-        cb4.w = chunk_check(cb4.x, cb4.y, cb4.z, round, 1);
-        cc4.x = f2u(xb); cc4.y = f2u(yb); cc4.z = f2u(zb);
-        cc4.w = chunk_check(cc4.x, cc4.y, cc4.z, round, 2);
+        u32x4 c0, c1, c2, c3;
+        c0.x = in.va; c0.y = in.vb; c0.z = in.bound;
+        c0.w = chunk_check(c0.x, c0.y, c0.z, round, 0);
+        c1.x = f2u(in.xa); c1.y = f2u(in.ya); c1.z = f2u(in.za);
+        c1.w = chunk_check(c1.x, c1.y, c1.z, round, 1);
+        c2.x = f2u(in.xb); c2.y = f2u(in.yb); c2.z = f2u(in.zb);
+        c2.w = chunk_check(c2.x, c2.y, c2.z, round, 2);
+        c3.x = in.ia; c3.y = in.ib; c3.z = 0u;
+        c3.w = chunk_check(c3.x, c3.y, c3.z, round, 3);
         const size_t so = (size_t)slot_of(w) * 16;
-        store_chunk(buf + so, ca);
-        store_chunk(buf + kChunkBytes + so, cb4);
-        store_chunk(buf + 2 * kChunkBytes + so, cc4);
+        store_chunk(buf + so, c0);
+        store_chunk(buf + kChunkBytes + so, c1);
+        store_chunk(buf + 2 * kChunkBytes + so, c2);
+        store_chunk(buf + 3 * kChunkBytes + so, c3);
     }
     FFPS_STAMP(prof, 2);
-    // ---- 2c. gather: lane L reads slots q*64+L = workgroups 4L+q ----
-    u32x4 ra[kRPL], rb[kRPL], rc[kRPL];
+    // ---- gather: lane L reads slots q*64+L = workgroups 4L+q ----
+    u32x4 ra[kRPL], rb[kRPL], rc[kRPL], rd[kRPL];
     bool gave_up = false;
     for (int spin = 0;; ++spin) {
-        load_chunks3(buf + (size_t)lane * 16, buf + kChunkBytes + (size_t)lane * 16,
-                     buf + 2 * kChunkBytes + (size_t)lane * 16, ra, rb, rc);
+        const char *p = buf + (size_t)lane * 16;
+        load_chunks4(p, p + kChunkBytes, p + 2 * kChunkBytes, p + 3 * kChunkBytes, ra, rb, rc, rd);
         bool all = true;
 #pragma unroll
         for (int q = 0; q < kRPL; ++q) {
-            bool ok = ra[q].w == chunk_check(ra[q].x, ra[q].y, ra[q].z, round, 0) &&
-                      rb[q].w == chunk_check(rb[q].x, rb[q].y, rb[q].z, round, 1) &&
-                      rc[q].w == chunk_check(rc[q].x, rc[q].y, rc[q].z, round, 2);
+            bool ok = chunk_ok(ra[q], round, 0) && chunk_ok(rb[q], round, 1) &&
+                      chunk_ok(rc[q], round, 2) && chunk_ok(rd[q], round, 3);
             all = all && (ok || lane * kRPL + q >= G);
         }
 #ifdef FFPS_PROFILE
@@ -212,46 +266,54 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
         if (lane == 0) __hip_atomic_store(status, -5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return -1;
     }
-    // candidate c = 2q + r of this lane: workgroup 4*lane + q, its r-th in index order
-    uint32_t cv[kCPL], lb = 0u;
+    // candidate c = 2q + r of this lane: workgroup 4*lane + q, its r-th entry
+    uint32_t cv[kCPL], ci[kCPL], lb = 0u;
     float cx[kCPL], cy[kCPL], cz[kCPL];
 #pragma unroll
     for (int q = 0; q < kRPL; ++q) {
-        bool present = lane * kRPL + q < G;  // absent records: value 0, bound 0
+        const bool present = lane * kRPL + q < G;  // absent records: value 0, bound 0
         cv[2 * q] = present ? ra[q].x : 0u;
         cv[2 * q + 1] = present ? ra[q].y : 0u;
         lb = umax(lb, present ? ra[q].z : 0u);
+        ci[2 * q] = present ? rd[q].x : kNoIndex;
+        ci[2 * q + 1] = present ? rd[q].y : kNoIndex;
         cx[2 * q] = u2f(rb[q].x); cy[2 * q] = u2f(rb[q].y); cz[2 * q] = u2f(rb[q].z);
         cx[2 * q + 1] = u2f(rc[q].x); cy[2 * q + 1] = u2f(rc[q].y); cz[2 * q + 1] = u2f(rc[q].z);
     }
-    // ---- 3. replay the greedy rule on the published candidates ----
+    // ---- replay the greedy rule on the published candidates ----
     const uint32_t Bound = wave_max_u32(lb);
-        // Hand pick number c of this round to the workers (one 16-byte LDS write) and
-    // note which candidate it was; `mine` holds in exactly one lane.
-    auto emit = [&](bool mine, int c, int cid, uint32_t vbits, float ex, float ey, float ez) {
+    // Hand pick number c of this round to the other waves (one 16-byte LDS write)
+    // and note its index and value; `mine` holds in exactly one lane.
+    auto emit = [&](bool mine, int c, uint32_t idx, uint32_t vbits, float ex, float ey, float ez) {
         if (mine) {
             u32x4 s;
             s.x = f2u(ex); s.y = f2u(ey); s.z = f2u(ez); s.w = (uint32_t)(npicked + c);
             lds_write16(pk_off + c * 16, s);
-            pk_id[c] = cid;
-            pk_val[c] = vbits;
+            L.pk_idx[c] = idx;
+            L.pk_val[c] = vbits;
         }
     };
-    uint32_t bv = cv[0];
-    int bq = 0;
+    auto lane_best = [&](uint32_t &bv, uint32_t &bi, int &bq) {
+        bv = cv[0]; bi = ci[0]; bq = 0;
 #pragma unroll
-    for (int q = 1; q < kCPL; ++q)
-        if (cv[q] > bv) {
-            bv = cv[q];
-            bq = q;
+        for (int q = 1; q < kCPL; ++q) {
+            const bool better = cv[q] > bv || (cv[q] == bv && ci[q] < bi);
+            bv = better ? cv[q] : bv;
+            bi = better ? ci[q] : bi;
+            bq = better ? q : bq;
         }
+    };
+    auto wmin = [](uint32_t v) { return wave_min_u32(v); };
+    uint32_t bv, bi;
+    int bq;
+    lane_best(bv, bi, bq);
     uint32_t V = wave_max_u32(bv);
     int cnt = 0;
     int pl;
     float px, py, pz;
     // Only candidates above the bound can be picked after the first pick, and
     // when the best candidate is above it the first pick is one of them too:
-    // compact them, in candidate (= index) order.
+    // compact them (in any order).
     int total = 0, before = 0;
     if (V > Bound && cap > 1) {
         const uint64_t lt = ((uint64_t)1 << lane) - 1;
@@ -264,10 +326,11 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
     }
     // With at most 128 live candidates whose values lie within 2^24 ulps above
     // the bound, value and position fit one 32-bit key
-    //   key = (value_bits - bound_bits) << 7 | (127 - position),
-    // so a single wave-wide max yields the best value AND, among equal values,
-    // the lowest position (= lowest index).  Values at or below the bound
-    // saturate to 0 and end the round.
+    //   key = (value_bits - bound_bits) << 7 | position,
+    // and a single wave-wide max yields the best value and a lane that holds it.
+    // Values at or below the bound saturate to 0 and end the round.  Whether other
+    // candidates hold the same value costs one ballot; only then is the index
+    // compared.
     const bool packed = total >= 1 && total <= 2 * kWave && V - Bound < (1u << 24);
 #ifdef FFPS_PROFILE
     if (prof && packed) prof->acc[total <= kWave ? 5 : 6] += 1;
@@ -277,11 +340,11 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
 #pragma unroll
         for (int q = 0; q < kCPL; ++q) {
             if (cv[q] > Bound) {
-                cmp_v[pos] = cv[q];
-                cmp_id[pos] = lane * kCPL + q;
-                cmp_x[pos] = cx[q];
-                cmp_y[pos] = cy[q];
-                cmp_z[pos] = cz[q];
+                L.cmp_v[pos] = cv[q];
+                L.cmp_i[pos] = ci[q];
+                L.cmp_x[pos] = cx[q];
+                L.cmp_y[pos] = cy[q];
+                L.cmp_z[pos] = cz[q];
                 ++pos;
             }
         }
@@ -289,22 +352,27 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
         if (total <= kWave) {
             // one candidate per lane: lane L takes position L
             const bool h = lane < total;
-            uint32_t v0 = h ? cmp_v[lane] : 0u;
-            int id0 = h ? cmp_id[lane] : 0;
-            float x0 = h ? cmp_x[lane] : 0.f, y0 = h ? cmp_y[lane] : 0.f,
-                  z0 = h ? cmp_z[lane] : 0.f;
-            const uint32_t inv = 127u - (uint32_t)lane;
+            uint32_t v0 = h ? L.cmp_v[lane] : 0u;
+            const uint32_t i0 = h ? L.cmp_i[lane] : kNoIndex;
+            const float x0 = h ? L.cmp_x[lane] : 0.f, y0 = h ? L.cmp_y[lane] : 0.f,
+                        z0 = h ? L.cmp_z[lane] : 0.f;
 #ifdef FFPS_PROFILE
             const uint64_t lc0 = clock64();
 #endif
             while (true) {
-                const uint32_t K = wave_max_u32((__builtin_elementwise_sub_sat(v0, Bound) << 7) | inv);
+                const uint32_t key = (__builtin_elementwise_sub_sat(v0, Bound) << 7) | (uint32_t)lane;
+                const uint32_t K = wave_max_u32(key);
                 if ((K >> 7) == 0) break;  // cannot happen for the first pick
-                pl = 127 - (int)(K & 127u);
+                const uint64_t tied = __builtin_amdgcn_ballot_w64((key >> 7) == (K >> 7));
+                pl = (int)(K & 127u);
+                if (__builtin_popcountll(tied) > 1) {  // several candidates share the best value
+                    const uint32_t imin = wave_min_u32((key >> 7) == (K >> 7) ? i0 : 0xffffffffu);
+                    pl = first_lane((key >> 7) == (K >> 7) && i0 == imin);
+                }
                 px = readlane_f(x0, pl);
                 py = readlane_f(y0, pl);
                 pz = readlane_f(z0, pl);
-                emit(lane == pl, cnt, id0, v0, x0, y0, z0);  // the winning lane hands over its own
+                emit(lane == pl, cnt, i0, v0, x0, y0, z0);  // the winning lane hands over its own
                 if (++cnt >= cap) break;
                 v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
             }
@@ -315,32 +383,45 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
             }
 #endif
         } else {
-            // two candidates per lane: lane L takes positions 2L and 2L+1
+            // two candidates per lane (positions 2L and 2L+1), the lower index first,
+            // so that a lane whose two values tie puts forward the right one
             const int p0 = 2 * lane, p1 = 2 * lane + 1;
             const bool h0 = p0 < total, h1 = p1 < total;
-            uint32_t v0 = h0 ? cmp_v[p0] : 0u, v1 = h1 ? cmp_v[p1] : 0u;
-            int id0 = h0 ? cmp_id[p0] : 0, id1 = h1 ? cmp_id[p1] : 0;
-            float x0 = h0 ? cmp_x[p0] : 0.f, y0 = h0 ? cmp_y[p0] : 0.f,
-                  z0 = h0 ? cmp_z[p0] : 0.f;
-            float x1 = h1 ? cmp_x[p1] : 0.f, y1 = h1 ? cmp_y[p1] : 0.f,
-                  z1 = h1 ? cmp_z[p1] : 0.f;
-            const uint32_t inv0 = 127u - (uint32_t)p0, inv1 = 127u - (uint32_t)p1;
+            uint32_t v0 = h0 ? L.cmp_v[p0] : 0u, v1 = h1 ? L.cmp_v[p1] : 0u;
+            uint32_t i0 = h0 ? L.cmp_i[p0] : kNoIndex, i1 = h1 ? L.cmp_i[p1] : kNoIndex;
+            float x0 = h0 ? L.cmp_x[p0] : 0.f, y0 = h0 ? L.cmp_y[p0] : 0.f, z0 = h0 ? L.cmp_z[p0] : 0.f;
+            float x1 = h1 ? L.cmp_x[p1] : 0.f, y1 = h1 ? L.cmp_y[p1] : 0.f, z1 = h1 ? L.cmp_z[p1] : 0.f;
+            if (i1 < i0) {
+                uint32_t tu;
+                float tf;
+                tu = v0; v0 = v1; v1 = tu;
+                tu = i0; i0 = i1; i1 = tu;
+                tf = x0; x0 = x1; x1 = tf;
+                tf = y0; y0 = y1; y1 = tf;
+                tf = z0; z0 = z1; z1 = tf;
+            }
 #ifdef FFPS_PROFILE
             const uint64_t lc0 = clock64();
 #endif
             while (true) {
-                const uint32_t k0 = (__builtin_elementwise_sub_sat(v0, Bound) << 7) | inv0;
-                const uint32_t k1 = (__builtin_elementwise_sub_sat(v1, Bound) << 7) | inv1;
-                // each lane puts forward the better of its two (keys are distinct)
-                const bool sec = k1 > k0;
+                const uint32_t d0 = __builtin_elementwise_sub_sat(v0, Bound);
+                const uint32_t d1 = __builtin_elementwise_sub_sat(v1, Bound);
+                const bool sec = d1 > d0;  // strict: equal values put the lower index forward
                 const float bx = sec ? x1 : x0, by = sec ? y1 : y0, bz = sec ? z1 : z0;
-                const uint32_t K = wave_max_u32(sec ? k1 : k0);
+                const uint32_t bidx = sec ? i1 : i0;
+                const uint32_t key = ((sec ? d1 : d0) << 7) | (uint32_t)lane;
+                const uint32_t K = wave_max_u32(key);
                 if ((K >> 7) == 0) break;
-                pl = (127 - (int)(K & 127u)) >> 1;
+                const uint64_t tied = __builtin_amdgcn_ballot_w64((key >> 7) == (K >> 7));
+                pl = (int)(K & 127u);
+                if (__builtin_popcountll(tied) > 1) {
+                    const uint32_t imin = wave_min_u32((key >> 7) == (K >> 7) ? bidx : 0xffffffffu);
+                    pl = first_lane((key >> 7) == (K >> 7) && bidx == imin);
+                }
                 px = readlane_f(bx, pl);
                 py = readlane_f(by, pl);
                 pz = readlane_f(bz, pl);
-                emit(lane == pl, cnt, sec ? id1 : id0, sec ? v1 : v0, bx, by, bz);
+                emit(lane == pl, cnt, bidx, sec ? v1 : v0, bx, by, bz);
                 if (++cnt >= cap) break;
                 v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
                 v1 = f2u(fminf(u2f(v1), sqdist(x1, y1, z1, px, py, pz)));
@@ -358,34 +439,24 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
         // packed key: work on all eight candidates per lane
         while (true) {
             if (cnt > 0) {
-                bv = cv[0];
-                bq = 0;
-#pragma unroll
-                for (int q = 1; q < kCPL; ++q)
-                    if (cv[q] > bv) {
-                        bv = cv[q];
-                        bq = q;
-                    }
+                lane_best(bv, bi, bq);
                 V = wave_max_u32(bv);
                 if (!(V > Bound)) break;
             }
-            pl = first_lane(bv == V);
-            int pq = readlane_i(bq, pl);
+            pl = best_lane(bv, bi, V, wmin);
+            const int pq = readlane_i(bq, pl);
             pick_xyz<kCPL>(cx, cy, cz, pq, pl, px, py, pz);
-            emit(lane == 0, cnt, pl * kCPL + pq, V, px, py, pz);
+            emit(lane == pl, cnt, bi, V, px, py, pz);
             if (++cnt >= cap) break;
 #pragma unroll
             for (int q = 0; q < kCPL; ++q)
                 cv[q] = f2u(fminf(u2f(cv[q]), sqdist(cx[q], cy[q], cz[q], px, py, pz)));
         }
     }
-    // the workgroup that owns a pick records it (same wave wrote pk_id / pk_val)
-    if (lane < cnt) {
-        const int cid = pk_id[lane];
-        if ((cid >> 1) == w) {
-            idx_out[npicked + lane] = (cid & 1) ? ib : ia;
-            if (md_out) md_out[npicked + lane] = u2f(pk_val[lane]);
-        }
+    // workgroup 0 records the picks (the same wave wrote pk_idx / pk_val)
+    if (w == 0 && lane < cnt) {
+        idx_out[npicked + lane] = (int32_t)L.pk_idx[lane];
+        if (md_out) md_out[npicked + lane] = u2f(L.pk_val[lane]);
     }
     return cnt;
 }

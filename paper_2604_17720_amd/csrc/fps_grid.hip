@@ -1,8 +1,11 @@
 // k_fps_grid: exact FPS (Sec. 3.1, Eq. 1) of ONE cloud spread over all CUs,
 // points resident in registers.
 //
-// Each of G co-resident workgroups keeps a contiguous slice of the cloud and
-// its running minimum distances in registers for the whole call.  A workgroup
+// Each of G co-resident workgroups keeps every G-th point of the cloud (point i
+// belongs to workgroup i mod G) and its running minimum distance in registers
+// for the whole call.  The strided assignment spreads any run of consecutive
+// indices over all workgroups, so an input that is already in farthest-point
+// order (a layer of a stage chain) yields as many picks per round as any other.  A workgroup
 // is one COMMUNICATION wave (wave 0) plus NWK WORKER waves that own the points.
 // Waves i and i+4 of a workgroup share a SIMD, so waves 4, 8 and 12 exit at
 // once: the communication wave, whose dependent chain sets the pace, then has
@@ -26,8 +29,7 @@ namespace ffps {
 namespace {
 
 struct WaveTop {  // a worker wave's two best points and the bound on its others
-    uint32_t v1, v2, v3;
-    int i1, i2;
+    Top3 t;
     float x1, y1, z1, x2, y2, z2;
     uint32_t pad;
 };
@@ -35,18 +37,12 @@ struct WaveTop {  // a worker wave's two best points and the bound on its others
 struct GridArgs {
     const float *xyz;
     int N, M, start;
-    int chunk;  // points per workgroup
     int32_t *idx_out;
     float *md_out;
     char *exchange;  // two buffers of kBufBytes
     int *status;
     int max_picks;
 };
-
-// Largest of up to 16 values held by lanes 0..15 (other lanes pass 0), wave-uniform.
-__device__ __forceinline__ uint32_t row_max_uniform(uint32_t v) {
-    return (uint32_t)readlane_i((int)row16_max_u32(v), 15);
-}
 
 // Number of waves a workgroup with NWK worker waves launches: wave 0
 // communicates, waves 4, 8, 12 exit at once, the rest work.
@@ -67,8 +63,6 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
     const int wave = tid / kWave;
     if (wave != 0 && (wave & 3) == 0) return;  // leaves the communication wave's SIMD to it
 
-    const int lo = w * a.chunk;
-    const int hi = min(a.N, lo + a.chunk);
     // One pick handed from the communication wave to the workers is a single
     // 16-byte LDS word {x, y, z, seq}: written and read by one instruction each, so
     // a reader that sees the expected seq also sees its coordinates.
@@ -98,16 +92,20 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
     if (wave != 0) {
         // =============================== worker ===============================
         const int wk = wave - 1 - wave / 4;  // 0 .. NWK-1
-        const int first = lo + (wk * kWave + lane) * P;
+        constexpr int NTW = NWK * kWave;
+        const int t = wk * kWave + lane;      // worker thread number
+        // element j of this lane is point (j * NTW + t) * G + w: ascending in j
+        auto index_of = [&](int j) { return (uint32_t)((j * NTW + t) * G + w); };
         float x[P], y[P], z[P], m[P];
 #pragma unroll
         for (int j = 0; j < P; ++j) {
-            int i = first + j;
-            bool ok = i < hi;
+            const uint32_t i = index_of(j);
+            const bool ok = i < (uint32_t)a.N;
             x[j] = ok ? a.xyz[3 * (size_t)i + 0] : 0.f;
             y[j] = ok ? a.xyz[3 * (size_t)i + 1] : 0.f;
             z[j] = ok ? a.xyz[3 * (size_t)i + 2] : 0.f;
-            m[j] = ok ? __builtin_inff() : 0.f;  // padding: value 0, never preferred
+            // padding: value 0 and an index beyond every real one, never preferred
+            m[j] = ok ? __builtin_inff() : 0.f;
         }
         int applied = 0;  // picks applied so far = sequence number of the next pick
         for (int batch = 0;; ++batch) {
@@ -143,26 +141,24 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
                 j1 = g1 ? j : j1;
                 a1 = fmaxf(a1, v);
             }
-            // ---- 1c. wave top two + bound ----
-            uint32_t W1 = wave_max_u32(f2u(a1));
-            int l1 = first_lane(f2u(a1) == W1);
-            uint32_t b = lane == l1 ? f2u(a2) : f2u(a1);
-            uint32_t W2 = wave_max_u32(b);
-            int l2 = first_lane(b == W2);
-            uint32_t c = lane == l1 ? (l1 == l2 ? f2u(a3) : f2u(a2)) : (lane == l2 ? f2u(a2) : f2u(a1));
-            uint32_t W3 = wave_max_u32(c);
-            int e1 = readlane_i(j1, l1);
-            int e2 = readlane_i(l1 == l2 ? j2 : j1, l2);
+            // ---- 1c. wave top two + bound (equal values: lowest index first) ----
+            Top3 mine;
+            mine.v1 = f2u(a1); mine.v2 = f2u(a2); mine.v3 = f2u(a3);
+            mine.i1 = index_of(j1); mine.i2 = index_of(j2);
+            int l1, l2;
+            bool s2;
+            const Top3 wt = merge_top3(mine, true, lane, [](uint32_t v) { return wave_max_u32(v); },
+                                       [](uint32_t v) { return wave_min_u32(v); }, l1, l2, s2);
+            const int e1 = readlane_i(j1, l1);
+            const int e2 = readlane_i(s2 ? j2 : j1, l2);
             float x1, y1, z1, x2, y2, z2;
             pick_xyz<P>(x, y, z, e1, l1, x1, y1, z1);
             pick_xyz<P>(x, y, z, e2, l2, x2, y2, z2);
             if (lane == 0) {
-                WaveTop &t = wtop[wk];
-                t.v1 = W1; t.v2 = W2; t.v3 = W3;
-                t.i1 = lo + (wk * kWave + l1) * P + e1;
-                t.i2 = lo + (wk * kWave + l2) * P + e2;
-                t.x1 = x1; t.y1 = y1; t.z1 = z1;
-                t.x2 = x2; t.y2 = y2; t.z2 = z2;
+                WaveTop &o = wtop[wk];
+                o.t = wt;
+                o.x1 = x1; o.y1 = y1; o.z1 = z1;
+                o.x2 = x2; o.y2 = y2; o.z2 = z2;
             }
             __syncthreads();  // wave tops ready for the communication wave
         }
@@ -186,38 +182,20 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
         FFPS_STAMP(prof, 1);
         // ---- 2a. workgroup top two + bound from the worker waves' triples ----
         const bool act = lane < NWK;
-        const int wl = act ? lane : 0;
-        uint32_t t1 = act ? wtop[wl].v1 : 0u;
-        uint32_t t2 = act ? wtop[wl].v2 : 0u;
-        uint32_t t3 = act ? wtop[wl].v3 : 0u;
-        uint32_t G1 = row_max_uniform(t1);
-        int w1 = first_lane(act && t1 == G1);
-        uint32_t bb = act ? (lane == w1 ? t2 : t1) : 0u;
-        uint32_t G2 = row_max_uniform(bb);
-        int w2 = first_lane(act && bb == G2);
-        uint32_t cc = act ? (lane == w1 ? (w1 == w2 ? t3 : t2) : (lane == w2 ? t2 : t1)) : 0u;
-        uint32_t G3 = row_max_uniform(cc);
-        // candidate 1 = wave w1's first; candidate 2 = wave w2's first, or w1's second
-        int gi1 = wtop[w1].i1;
-        float gx1 = wtop[w1].x1, gy1 = wtop[w1].y1, gz1 = wtop[w1].z1;
-        const bool same = w1 == w2;
-        int gi2 = same ? wtop[w1].i2 : wtop[w2].i1;
-        float gx2 = same ? wtop[w1].x2 : wtop[w2].x1;
-        float gy2 = same ? wtop[w1].y2 : wtop[w2].y1;
-        float gz2 = same ? wtop[w1].z2 : wtop[w2].z1;
-        // list the two candidates in index order (see "Ties" above)
-        uint32_t va = G1, vb = G2;
-        int ia = gi1, ib = gi2;
-        float xa = gx1, ya = gy1, za = gz1, xb = gx2, yb = gy2, zb = gz2;
-        if (gi2 < gi1) {
-            va = G2; vb = G1; ia = gi2; ib = gi1;
-            xa = gx2; ya = gy2; za = gz2; xb = gx1; yb = gy1; zb = gz1;
-        }
-        // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
+        int w1, w2;
+        bool s2w;
+        const Top3 g3 = merge_top3(wtop[act ? lane : 0].t, act, lane,
+                                   [](uint32_t v) { return row_max_uniform(v); },
+                                   [](uint32_t v) { return row_min_uniform(v); }, w1, w2, s2w);
+        // candidate a = wave w1's first; candidate b = wave w2's first, or w1's second
         RoundInput in;
-        in.va = va; in.vb = vb; in.bound = G3;
-        in.xa = xa; in.ya = ya; in.za = za; in.xb = xb; in.yb = yb; in.zb = zb;
-        in.ia = ia; in.ib = ib;
+        in.va = g3.v1; in.vb = g3.v2; in.bound = g3.v3;
+        in.ia = g3.i1; in.ib = g3.i2;
+        in.xa = wtop[w1].x1; in.ya = wtop[w1].y1; in.za = wtop[w1].z1;
+        in.xb = s2w ? wtop[w1].x2 : wtop[w2].x1;
+        in.yb = s2w ? wtop[w1].y2 : wtop[w2].y1;
+        in.zb = s2w ? wtop[w1].z2 : wtop[w2].z1;
+        // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
         const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
         const int cnt = exchange_round(L, a.exchange, G, w, lane, round, in, npicked, cap, a.idx_out,
                                        a.md_out, a.status, prof);
@@ -273,12 +251,12 @@ hipError_t launch_fps_grid(const float *xyz, int N, int M, int start, int32_t *i
     if (G < 1) G = 1;
     GridArgs a;
     a.xyz = xyz; a.N = N; a.M = M; a.start = start;
-    a.chunk = (N + G - 1) / G;
+    const int per_wg = (N + G - 1) / G;  // most points any workgroup holds
     a.idx_out = idx; a.md_out = md;
     a.exchange = (char *)exchange; a.status = status;
     a.max_picks = max_picks < 1 ? 1 : (max_picks > kMaxPicksPerRound ? kMaxPicksPerRound : max_picks);
 #define FFPS_GRID_CASE(NWK, P) \
-    if (a.chunk <= (NWK) * kWave * (P)) return launch_t<NWK, P>(a, G, s);
+    if (per_wg <= (NWK) * kWave * (P)) return launch_t<NWK, P>(a, G, s);
     FFPS_GRID_CASE(3, 1)
     FFPS_GRID_CASE(3, 2)
     FFPS_GRID_CASE(3, 3)

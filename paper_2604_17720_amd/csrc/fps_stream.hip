@@ -10,8 +10,8 @@
 // point are paid once per round, not once per pick.
 //
 // Lanes take groups of four consecutive points (three 16-byte loads of
-// coordinates, one of distances), so index order is not lane order here and
-// reductions break value ties on the index explicitly.
+// coordinates, one of distances); slices stay contiguous so that every load of
+// a wave is coalesced.
 #include "fps_exchange.h"
 
 namespace ffps {
@@ -19,7 +19,6 @@ namespace ffps {
 namespace {
 
 constexpr int kStreamThreads = 1024;
-constexpr uint32_t kNoIndex = 0x7fffffffu;
 
 struct StreamArgs {
     const float *xyz;
@@ -33,36 +32,6 @@ struct StreamArgs {
     int max_picks;
     int aligned16;  // xyz is 16-byte aligned
 };
-
-struct Top3 {  // two best (value, index) pairs and the third value, in (value desc, index asc) order
-    uint32_t v1, v2, v3;
-    uint32_t i1, i2;
-};
-
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return ~wave_max_u32(~v); }
-__device__ __forceinline__ uint32_t row_max_uniform(uint32_t v) {
-    return (uint32_t)readlane_i((int)row16_max_u32(v), 15);
-}
-__device__ __forceinline__ uint32_t row_min_uniform(uint32_t v) { return ~row_max_uniform(~v); }
-
-// Merge the Top3 of the participating lanes (`act`) into one; MAXF / MINF reduce
-// over those lanes and return wave-uniform values.
-template <typename MAXF, typename MINF>
-__device__ __forceinline__ Top3 merge_top3(const Top3 &t, bool act, int lane, MAXF maxf, MINF minf) {
-    Top3 r;
-    const uint32_t a1 = act ? t.v1 : 0u, a2 = act ? t.v2 : 0u, a3 = act ? t.v3 : 0u;
-    const uint32_t i1 = act ? t.i1 : kNoIndex, i2 = act ? t.i2 : kNoIndex;
-    r.v1 = maxf(a1);
-    r.i1 = minf(a1 == r.v1 ? i1 : kNoIndex);
-    const int l1 = first_lane(act && a1 == r.v1 && i1 == r.i1);
-    const uint32_t b = lane == l1 ? a2 : a1, bi = lane == l1 ? i2 : i1;
-    r.v2 = maxf(b);
-    r.i2 = minf(b == r.v2 ? bi : kNoIndex);
-    const int l2 = first_lane(act && b == r.v2 && bi == r.i2);
-    const uint32_t c = lane == l1 ? (l1 == l2 ? a3 : a2) : (lane == l2 ? a2 : a1);
-    r.v3 = maxf(c);
-    return r;
-}
 
 __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
     constexpr int NT = kStreamThreads, NW = NT / kWave;
@@ -104,7 +73,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
         // ---- 1. one pass over the slice ----
         // running top three of this lane; -1 sorts below every distance
         float t1 = -1.f, t2 = -1.f, t3 = -1.f;
-        uint32_t j1 = kNoIndex, j2 = kNoIndex;
+        uint32_t j1 = 0xffffffffu, j2 = 0xffffffffu;
         auto track = [&](float v, uint32_t i) {
             const bool g1 = v > t1, g2 = v > t2;  // strict: this lane visits indices in ascending order
             t3 = fmaxf(t3, fminf(v, t2));
@@ -184,26 +153,28 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
         Top3 mine;
         mine.v1 = f2u(fmaxf(t1, 0.f)); mine.v2 = f2u(fmaxf(t2, 0.f)); mine.v3 = f2u(fmaxf(t3, 0.f));
         mine.i1 = j1; mine.i2 = j2;
+        int l1, l2;
+        bool s2;
         const Top3 wt = merge_top3(mine, true, lane, [](uint32_t v) { return wave_max_u32(v); },
-                                   [](uint32_t v) { return wave_min_u32(v); });
+                                   [](uint32_t v) { return wave_min_u32(v); }, l1, l2, s2);
         if (lane == 0) wtop[wave] = wt;
         __syncthreads();  // wave tops visible; every wave is done with the picks in L.pk
 
         if (wave == 0) {
             // ---- 2a. workgroup top two + bound ----
             const bool act = lane < NW;
+            int w1, w2;
+            bool s2w;
             const Top3 g3 = merge_top3(wtop[act ? lane : 0], act, lane,
                                        [](uint32_t v) { return row_max_uniform(v); },
-                                       [](uint32_t v) { return row_min_uniform(v); });
-            // in index order; an index that does not exist (slice of one point) sorts last
+                                       [](uint32_t v) { return row_min_uniform(v); }, w1, w2, s2w);
+            // an index that does not exist (slice of one point) has value 0
             RoundInput in;
-            const bool swap = g3.i2 < g3.i1;
-            const uint32_t ia = swap ? g3.i2 : g3.i1, ib = swap ? g3.i1 : g3.i2;
-            in.va = swap ? g3.v2 : g3.v1;
-            in.vb = swap ? g3.v1 : g3.v2;
-            in.bound = g3.v3;
-            in.ia = (int)ia; in.ib = (int)ib;
+            in.va = g3.v1; in.vb = g3.v2; in.bound = g3.v3;
+            const uint32_t ia = g3.i1, ib = g3.i2;
             const bool ea = ia < (uint32_t)a.N, eb = ib < (uint32_t)a.N;
+            in.ia = ea ? ia : kNoIndex;
+            in.ib = eb ? ib : kNoIndex;
             in.xa = ea ? a.xyz[3 * (size_t)(ea ? ia : 0) + 0] : 0.f;
             in.ya = ea ? a.xyz[3 * (size_t)(ea ? ia : 0) + 1] : 0.f;
             in.za = ea ? a.xyz[3 * (size_t)(ea ? ia : 0) + 2] : 0.f;
