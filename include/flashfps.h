@@ -56,7 +56,7 @@ extern "C" {
 /* Kernel variant; AUTO picks by (B, N). */
 #define FFPS_VARIANT_AUTO 0
 #define FFPS_VARIANT_WG 1     /* one workgroup per cloud, points resident in registers       */
-#define FFPS_VARIANT_GRID 2   /* one cloud across all CUs, points resident in registers      */
+#define FFPS_VARIANT_GRID 2   /* each cloud across many CUs, points resident in registers    */
 #define FFPS_VARIANT_STREAM 3 /* one cloud across all CUs, points streamed from HBM per pass */
 /* Benchmarking knob for the multi-workgroup variants: cap on the picks accepted
  * per exchange round (1 = one pick per pass over the points; 0 = library
@@ -145,10 +145,11 @@ int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_sta
 int ffps_last_status(const void *d_ws, void *stream);
 
 /*
- * Number of exchange rounds the last whole-device (GRID) kernel launched on
- * this workspace took (each round delivers one or more picks), or a negative
- * status as ffps_last_status.  0 if no such kernel ran.  Synchronises `stream`.
- * Diagnostic: M - 1 picks / rounds = picks per cross-workgroup exchange.
+ * Largest number of exchange rounds any cloud took in a GRID or STREAM kernel
+ * of the last call on this workspace (each round delivers one or more picks),
+ * or a negative status as ffps_last_status.  0 if no such kernel ran.
+ * Synchronises `stream`.  Diagnostic: for a single ffps_exact launch,
+ * (M - 1) / rounds = picks per cross-workgroup exchange.
  */
 int ffps_last_rounds(const void *d_ws, void *stream);
 

@@ -22,7 +22,7 @@ Workspace carve(int B, int N, int M) {
     Workspace w;
     size_t o = 0;
     w.status = o;   o += kAlign;
-    w.exchange = o; o += align_up(grid_exchange_bytes());
+    w.exchange = o; o += align_up((size_t)kMaxGridWG * grid_exchange_bytes_per_cloud());
     w.cxyz = o;     o += align_up((size_t)B * N * 3 * sizeof(float));
     w.loc = o;      o += align_up((size_t)B * M * sizeof(int32_t));
     w.bitmap = o;   o += align_up((size_t)B * ((N + 31) / 32) * sizeof(uint32_t));
@@ -81,15 +81,19 @@ int check_variant(int variant) {
 int clear_status(char *ws, const Workspace &w, hipStream_t s) {
     return hip_rc(launch_fill_zero(ws + w.status, kAlign, s));
 }
-int clear_exchange(char *ws, const Workspace &w, hipStream_t s) {
-    return hip_rc(launch_fill_zero(ws + w.exchange, grid_exchange_bytes(), s));
+int clear_exchange(char *ws, const Workspace &w, int clouds, hipStream_t s) {
+    return hip_rc(launch_fill_zero(ws + w.exchange, (size_t)clouds * grid_exchange_bytes_per_cloud(), s));
 }
 
 // Kernel variant that will run for clouds of N points, or a negative error.
 int resolve_variant(int B, int N, int variant, const Device &dev) {
     int v = variant_kind(variant);
     if (v == FFPS_VARIANT_AUTO) {
-        if (N <= wg_capacity() && (B >= 4 || N <= 2048))
+        // Small clouds, or so many clouds that each would get only a few workgroups:
+        // one workgroup per cloud.  Otherwise clusters of workgroups per cloud.
+        const bool fits_wg = N <= wg_capacity();
+        const bool fits_grid = N <= grid_capacity(dev.num_cu);
+        if (fits_wg && (N <= 2048 || !fits_grid || plan_fps_grid(B, N, dev.num_cu).wg_per_cloud < 16))
             v = FFPS_VARIANT_WG;
         else if (N <= grid_capacity(dev.num_cu))
             v = FFPS_VARIANT_GRID;
@@ -111,20 +115,23 @@ int run_exact(const float *xyz, int B, int N, int M, int start, int variant, int
     if (v == FFPS_VARIANT_WG)
         return hip_rc(launch_fps_wg(xyz, B, N, M, start, idx, idx_stride, md, md_stride, s));
     if (v == FFPS_VARIANT_GRID) {
-        for (int b = 0; b < B; ++b) {
-            int rc = clear_exchange(ws, w, s);
+        const GridPlan plan = plan_fps_grid(B, N, dev.num_cu);
+        for (int b = 0; b < B; b += plan.clouds_per_launch) {
+            const int clouds = B - b < plan.clouds_per_launch ? B - b : plan.clouds_per_launch;
+            int rc = clear_exchange(ws, w, clouds, s);
             if (rc) return rc;
-            hipError_t e = launch_fps_grid(xyz + (size_t)b * N * 3, N, M, start, idx + b * idx_stride,
-                                           md ? md + b * md_stride : nullptr,
+            hipError_t e = launch_fps_grid(xyz + (size_t)b * N * 3, clouds, N, M, start,
+                                           idx + b * idx_stride, idx_stride,
+                                           md ? md + b * md_stride : nullptr, md_stride,
                                            ws + w.exchange, (int *)(ws + w.status),
-                                           dev.num_cu, variant_picks(variant), s);
+                                           plan.wg_per_cloud, variant_picks(variant), s);
             if (e != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;
         }
         return FFPS_OK;
     }
     if (v == FFPS_VARIANT_STREAM) {
         for (int b = 0; b < B; ++b) {
-            int rc = clear_exchange(ws, w, s);
+            int rc = clear_exchange(ws, w, 1, s);
             if (rc) return rc;
             hipError_t e = launch_fps_stream(xyz + (size_t)b * N * 3, (float *)(ws + w.mind) + (size_t)b * N,
                                              N, M, start, idx + b * idx_stride,
@@ -309,7 +316,7 @@ int ffps_barrier_probe(int iters, void *d_ws, size_t ws_bytes, void *stream, flo
     char *ws = (char *)d_ws;
     int rc = clear_status(ws, w, s);
     if (rc) return rc;
-    if ((rc = clear_exchange(ws, w, s))) return rc;
+    if ((rc = clear_exchange(ws, w, 1, s))) return rc;
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
         return FFPS_ERR_LAUNCH_FAILED;

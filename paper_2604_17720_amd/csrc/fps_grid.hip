@@ -34,12 +34,15 @@ struct WaveTop {  // a worker wave's two best points and the bound on its others
     uint32_t pad;
 };
 
-struct GridArgs {
+struct GridArgs {  // pointers are those of the first cloud of the launch
     const float *xyz;
     int N, M, start;
+    int wg_per_cloud;  // the grid holds (clouds of this launch) x wg_per_cloud workgroups
     int32_t *idx_out;
+    long idx_stride;   // elements between the outputs of consecutive clouds
     float *md_out;
-    char *exchange;  // two buffers of kBufBytes
+    long md_stride;
+    char *exchange;    // per cloud: two buffers of kBufBytes
     int *status;
     int max_picks;
 };
@@ -49,15 +52,23 @@ struct GridArgs {
 __host__ __device__ constexpr int grid_waves(int nwk) { return nwk + nwk / 3; }
 
 template <int NWK, int P>
-__global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a) {
+__global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_in) {
     static_assert(NWK % 3 == 0 && NWK >= 3 && NWK <= 12, "worker waves come in threes");
     __shared__ WaveTop wtop[NWK];
     __shared__ RoundLds L;
     __shared__ int fin[2];  // {batch id, picks emitted in total once that batch is complete}
     __shared__ int s_abort;
 
-    const int G = gridDim.x;
-    const int w = blockIdx.x;
+    // A launch may carry several clouds: each gets a cluster of wg_per_cloud
+    // consecutive workgroups with its own exchange area; clusters never interact.
+    GridArgs a = a_in;
+    const int G = a.wg_per_cloud;
+    const int cloud = blockIdx.x / G;
+    const int w = blockIdx.x - cloud * G;
+    a.xyz += (size_t)cloud * a.N * 3;
+    a.idx_out += cloud * a.idx_stride;
+    if (a.md_out) a.md_out += cloud * a.md_stride;
+    a.exchange += (size_t)cloud * 2 * kBufBytes;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
@@ -171,7 +182,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
     RoundProf *prof = nullptr;
 #ifdef FFPS_PROFILE
     RoundProf prof_store = {};
-    if (w == 0) prof = &prof_store;
+    if (w == 0 && cloud == 0) prof = &prof_store;
     prof_store.last = wall_clock64();
     const uint64_t prof_w0 = prof_store.last, prof_c0 = clock64();
 #endif
@@ -215,8 +226,10 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
         FFPS_STAMP(prof, 4);
     }
     if (w == 0 && lane == 0) {
-        a.status[1] = (int)round;  // exchange rounds this launch took
+        // exchange rounds this launch took (the largest count among its clouds)
+        __hip_atomic_fetch_max(a.status + 1, (int)round, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #ifdef FFPS_PROFILE
+        if (cloud == 0)
         for (int i = 0; i < 8; ++i) a.status[8 + i] = (int)prof_store.acc[i];
         for (int i = 0; i < 4; ++i) a.status[20 + i] = (int)prof_store.loop[i];
         a.status[16] = (int)(wall_clock64() - prof_w0);       // 10 ns units
@@ -226,37 +239,56 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a)
 }
 
 template <int NWK, int P>
-hipError_t launch_t(GridArgs &a, int G, hipStream_t s) {
+hipError_t launch_t(GridArgs &a, int num_wg, hipStream_t s) {
     void *params[] = {&a};
-    return hipLaunchCooperativeKernel((const void *)k_fps_grid<NWK, P>, dim3(G),
+    return hipLaunchCooperativeKernel((const void *)k_fps_grid<NWK, P>, dim3(num_wg),
                                       dim3(kWave * grid_waves(NWK)), params, 0, s);
 }
 
+constexpr int kMaxPointsPerWG = 12 * kWave * 16;
+
 }  // namespace
 
-size_t grid_exchange_bytes() { return 2 * kBufBytes; }
+size_t grid_exchange_bytes_per_cloud() { return 2 * kBufBytes; }
 
 long grid_capacity(int num_cu) {
     int G = num_cu < kMaxGridWG ? num_cu : kMaxGridWG;
-    return (long)G * 12 * kWave * 16;
+    return (long)G * kMaxPointsPerWG;
 }
 
-hipError_t launch_fps_grid(const float *xyz, int N, int M, int start, int32_t *idx, float *md,
-                           void *exchange, int *status, int num_cu, int max_picks,
-                           hipStream_t s) {
-    int maxG = num_cu < kMaxGridWG ? num_cu : kMaxGridWG;
-    // at least 128 points per workgroup before another CU is worth a record
-    int G = (N + 127) / 128;
-    if (G > maxG) G = maxG;
-    if (G < 1) G = 1;
+GridPlan plan_fps_grid(int B, int N, int num_cu) {
+    const int maxG = num_cu < kMaxGridWG ? num_cu : kMaxGridWG;
+    // at least 128 points per workgroup before another CU is worth a record ...
+    int want = (N + 127) / 128;
+    if (want > maxG) want = maxG;
+    // ... but rather all clouds in one launch than few clouds on many workgroups
+    int share = maxG / (B < maxG ? B : maxG);
+    if (share < 1) share = 1;
+    int g = want < share ? want : share;
+    const int need = (N + kMaxPointsPerWG - 1) / kMaxPointsPerWG;  // registers must hold the cloud
+    if (g < need) g = need;
+    GridPlan p;
+    p.wg_per_cloud = g;
+    p.clouds_per_launch = maxG / g < 1 ? 1 : maxG / g;
+    if (p.clouds_per_launch > B) p.clouds_per_launch = B;
+    return p;
+}
+
+hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start, int32_t *idx,
+                           long idx_stride, float *md, long md_stride, void *exchange, int *status,
+                           int wg_per_cloud, int max_picks, hipStream_t s) {
+    const int G = wg_per_cloud;
     GridArgs a;
     a.xyz = xyz; a.N = N; a.M = M; a.start = start;
-    const int per_wg = (N + G - 1) / G;  // most points any workgroup holds
-    a.idx_out = idx; a.md_out = md;
+    a.wg_per_cloud = G;
+    a.idx_out = idx; a.idx_stride = idx_stride;
+    a.md_out = md; a.md_stride = md_stride;
     a.exchange = (char *)exchange; a.status = status;
     a.max_picks = max_picks < 1 ? 1 : (max_picks > kMaxPicksPerRound ? kMaxPicksPerRound : max_picks);
+    const int per_wg = (N + G - 1) / G;  // most points any workgroup holds
+    const int num_wg = clouds * G;
 #define FFPS_GRID_CASE(NWK, P) \
-    if (per_wg <= (NWK) * kWave * (P)) return launch_t<NWK, P>(a, G, s);
+    if (per_wg <= (NWK) * kWave * (P)) return launch_t<NWK, P>(a, num_wg, s);
     FFPS_GRID_CASE(3, 1)
     FFPS_GRID_CASE(3, 2)
     FFPS_GRID_CASE(3, 3)

@@ -11,17 +11,25 @@ int wg_capacity();  // largest N the register-resident single-workgroup kernel h
 hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, int32_t *idx,
                          long idx_stride, float *md, long md_stride, hipStream_t s);
 
-// ---- fps_grid.hip: one cloud over the whole device --------------------------
-constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a grid launch may use
+// ---- fps_grid.hip: clouds spread over the whole device, resident in registers ----
+constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a launch may use
 constexpr int kMaxPicksPerRound = 64;
-size_t grid_exchange_bytes();        // bytes of the exchange area (two record buffers)
-long grid_capacity(int num_cu);      // largest N the register-resident grid kernel holds
-// One cloud.  `exchange` must have been cleared (all zero) on the same stream.
-// status[0] receives an error code if a workgroup gives up, status[1] the
-// number of exchange rounds the launch took.
-hipError_t launch_fps_grid(const float *xyz, int N, int M, int start, int32_t *idx, float *md,
-                           void *exchange, int *status, int num_cu, int max_picks,
-                           hipStream_t s);
+size_t grid_exchange_bytes_per_cloud();  // bytes of one cloud's exchange area (two record buffers)
+long grid_capacity(int num_cu);          // largest N the register-resident grid kernel holds
+// How B clouds of N points are laid over the device: workgroups per cloud, and
+// how many clouds one launch carries (each cloud on its own cluster of workgroups).
+struct GridPlan {
+    int wg_per_cloud;
+    int clouds_per_launch;
+};
+GridPlan plan_fps_grid(int B, int N, int num_cu);
+// `clouds` clouds (densely packed, outputs idx_stride / md_stride apart) in one
+// launch.  `exchange` needs clouds * grid_exchange_bytes_per_cloud() bytes, cleared
+// (all zero) on the same stream.  status[0] receives an error code if a
+// workgroup gives up, status[1] the largest number of exchange rounds a cloud took.
+hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start, int32_t *idx,
+                           long idx_stride, float *md, long md_stride, void *exchange, int *status,
+                           int wg_per_cloud, int max_picks, hipStream_t s);
 
 // ---- fps_stream.hip: one cloud over the whole device, streamed from HBM ------
 // `mind` is an [N] fp32 scratch array; `exchange` and `status` as for the grid kernel.

@@ -193,7 +193,8 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
         if (s_abort) return;
         npicked += s_cnt;
     }
-    if (w == 0 && tid == 0) a.status[1] = (int)round;
+    if (w == 0 && tid == 0)
+        __hip_atomic_fetch_max(a.status + 1, (int)round, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace

@@ -82,6 +82,16 @@ def test_ragged_sizes_and_seeds(fb, oracle, variant, n, m, start):
     _check_exact(fb, oracle, x, m, start, variant)
 
 
+@pytest.mark.parametrize("b,n,m", [(8, 16384, 600), (40, 3001, 400), (300, 200, 150), (3, 50000, 300),
+                                   (17, 9000, 257)])
+def test_grid_clusters_of_workgroups_per_cloud(fb, oracle, b, n, m):
+    """Several clouds in one launch, each on its own cluster of workgroups; more
+    clouds than the device has workgroups go out in several launches."""
+    x = np.stack([inputs.planes_and_clusters(n, 77000 + 13 * i) for i in range(b)])
+    _check_exact(fb, oracle, x, m, 0, GRID)
+    _check_exact(fb, oracle, x, min(m, 64), n - 1, 0)
+
+
 @pytest.mark.parametrize("n,m", [(30000, 500), (70001, 900), (262144, 64), (300001, 300)])
 def test_grid_multi_point_per_lane(fb, oracle, n, m):
     x = inputs.make_config(4, N=n)[0]
