@@ -137,6 +137,20 @@ int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_sta
                        int variant, int32_t *d_idx, void *d_ws, size_t ws_bytes, void *stream);
 
 /*
+ * What the layer after a sampling stage consumes (Sec. 1: each stage samples,
+ * then aggregates features around the samples): the rows of a per-point fp32
+ * array at the sampled indices, in sample order.
+ *   d_rows  in  [B][N][C] fp32 (C = 3 for coordinates, or any feature width)
+ *   d_idx   in  int32, S indices per cloud, cloud b at d_idx + b * idx_stride
+ *               (a stage of ffps_cached_stages: pass its offset and the row
+ *               length sum(M_stages) as idx_stride); every index in [0, N)
+ *   d_out   out [B][S][C]
+ * B <= 65535.  Needs no workspace.
+ */
+int ffps_gather_rows(const float *d_rows, int B, int N, int C, const int32_t *d_idx, long idx_stride,
+                     int S, float *d_out, void *stream);
+
+/*
  * Status word the kernels of the last call on this workspace left behind:
  * synchronises `stream`, copies one int from the workspace and returns it
  * (FFPS_OK, or FFPS_ERR_TIMEOUT when a workgroup stopped waiting for another;

@@ -36,7 +36,7 @@ def variant_with_picks(variant: int, picks: int) -> int:
 
 EXPORTS = ["ffps_version", "ffps_strerror", "ffps_prune_sizes", "ffps_workspace_bytes",
            "ffps_exact", "ffps_prune", "ffps_cached_stages", "ffps_last_status",
-           "ffps_last_rounds", "ffps_barrier_probe"]
+           "ffps_last_rounds", "ffps_barrier_probe", "ffps_gather_rows"]
 
 
 class FlashFPSError(RuntimeError):
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
                                          ctypes.c_uint, c_int, c_int, c_vp, c_vp, c_sz, c_vp]
         L.ffps_last_status.argtypes = [c_vp, c_vp]
         L.ffps_last_rounds.argtypes = [c_vp, c_vp]
+        L.ffps_gather_rows.argtypes = [c_vp, c_int, c_int, c_int, c_vp, ctypes.c_long, c_int, c_vp, c_vp]
         L.ffps_barrier_probe.argtypes = [c_int, c_vp, c_sz, c_vp, ctypes.POINTER(ctypes.c_float)]
         for n in EXPORTS:
             if n not in ("ffps_strerror",):
@@ -214,3 +215,24 @@ def ffps_barrier_probe(iters, workspace=None, stream=None) -> float:
     if rc:
         raise FlashFPSError(rc, "ffps_barrier_probe")
     return out.value
+
+
+def ffps_gather_rows(rows, idx, stream=None):
+    """rows: CUDA float32 [B,N,C]; idx: CUDA int32 [B,S] (may be a column slice of a
+    wider tensor, e.g. one stage of ffps_cached_stages).  Returns float32 [B,S,C]."""
+    torch = _torch()
+    if not (rows.is_cuda and rows.dtype == torch.float32 and rows.is_contiguous() and rows.dim() == 3):
+        raise ValueError("rows must be a contiguous float32 CUDA tensor [B,N,C]")
+    if not (idx.is_cuda and idx.dtype == torch.int32 and idx.dim() == 2 and idx.stride(1) == 1):
+        raise ValueError("idx must be an int32 CUDA tensor [B,S] with unit inner stride")
+    B, N, C = (int(v) for v in rows.shape)
+    S = int(idx.shape[1])
+    if int(idx.shape[0]) != B:
+        raise ValueError("batch sizes differ")
+    stride = int(idx.stride(0)) if B > 1 else max(int(idx.stride(0)), S)
+    out = torch.empty((B, S, C), dtype=torch.float32, device=rows.device)
+    rc = lib().ffps_gather_rows(rows.data_ptr(), B, N, C, idx.data_ptr(), stride, S, out.data_ptr(),
+                                _stream(torch, stream))
+    if rc:
+        raise FlashFPSError(rc, "ffps_gather_rows")
+    return out

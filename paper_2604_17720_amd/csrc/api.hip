@@ -306,6 +306,15 @@ int ffps_last_status(const void *d_ws, void *stream) {
     return st;
 }
 
+int ffps_gather_rows(const float *d_rows, int B, int N, int C, const int32_t *d_idx, long idx_stride,
+                     int S, float *d_out, void *stream) {
+    if (!d_rows || !d_idx || !d_out) return FFPS_ERR_INVALID_ARG;
+    if (B < 1 || B > 65535 || N < 1 || C < 1 || S < 1 || idx_stride < S) return FFPS_ERR_INVALID_ARG;
+    Device dev = query_device();
+    if (dev.ok) return dev.ok;
+    return hip_rc(launch_gather_rows(d_rows, B, N, C, d_idx, idx_stride, S, d_out, (hipStream_t)stream));
+}
+
 int ffps_barrier_probe(int iters, void *d_ws, size_t ws_bytes, void *stream, float *us_per_barrier) {
     if (!d_ws || !us_per_barrier || iters < 1 || iters > (1 << 20)) return FFPS_ERR_INVALID_ARG;
     Workspace w = carve(1, 1, 1);

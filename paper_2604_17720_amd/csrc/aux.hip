@@ -91,17 +91,25 @@ __global__ __launch_bounds__(1024) void k_fill(int N, int k, int R, int32_t *__r
         part[tid] += v;
         __syncthreads();
     }
+    // Rank r is taken by fill slot j = ceil(r*R/F) iff floor(j*F/R) == r, i.e. iff
+    // acc = j*F - r*R lies in [0, R).  One division finds j for the thread's first
+    // rank; from rank to rank acc drops by R and, when it goes negative, j steps up.
     long r = part[tid] - cnt;  // rank of this thread's first free index
     const long F = (long)N - k;
+    long j = (r * R + F - 1) / F;
+    long acc = j * F - r * R;
     for (int wd = w0; wd < w1; ++wd) {
         uint32_t valid = (wd == words - 1 && (N & 31)) ? ((1u << (N & 31)) - 1u) : 0xffffffffu;
         uint32_t free_bits = ~bm[wd] & valid;
         while (free_bits) {
             int bit = __ffs(free_bits) - 1;
             free_bits &= free_bits - 1;
-            long j = (r * R + F - 1) / F;
-            if (j < R && (j * F) / R == r) idx[k + j] = wd * 32 + bit;
-            ++r;
+            if (acc < R && j < R) idx[k + j] = wd * 32 + bit;
+            acc -= R;
+            if (acc < 0) {
+                ++j;
+                acc += F;
+            }
         }
     }
 }
@@ -116,6 +124,23 @@ __global__ void k_gather_points(const float *__restrict__ xyz, int N, const int3
         out[3 * (size_t)j + 0] = src[3 * (size_t)c + 0];
         out[3 * (size_t)j + 1] = src[3 * (size_t)c + 1];
         out[3 * (size_t)j + 2] = src[3 * (size_t)c + 2];
+    }
+}
+
+// out[b][j][0..C) = rows[b][sel[b][j]][0..C): one thread per output float, so
+// consecutive threads write consecutive addresses.
+__global__ void k_gather_rows(const float *__restrict__ rows, int N, int C,
+                              const int32_t *__restrict__ sel, long sel_stride, int S,
+                              float *__restrict__ out) {
+    const int b = blockIdx.y;
+    const float *src = rows + (size_t)b * N * C;
+    float *dst = out + (size_t)b * S * C;
+    const size_t total = (size_t)S * C;
+    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < total;
+         e += (size_t)gridDim.x * blockDim.x) {
+        const size_t j = e / C;
+        const int c = (int)(e - j * C);
+        dst[e] = src[(size_t)sel[b * sel_stride + j] * C + c];
     }
 }
 
@@ -200,6 +225,13 @@ hipError_t launch_gather_points(const float *xyz, int B, int N, const int32_t *s
                                 int S, float *dst, hipStream_t s) {
     hipLaunchKernelGGL(k_gather_points, dim3(blocks_for(S), B), dim3(kT), 0, s, xyz, N, sel,
                        sel_stride, S, dst);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const float *rows, int B, int N, int C, const int32_t *sel,
+                              long sel_stride, int S, float *out, hipStream_t s) {
+    hipLaunchKernelGGL(k_gather_rows, dim3(blocks_for((size_t)S * C), B), dim3(kT), 0, s, rows, N, C,
+                       sel, sel_stride, S, out);
     return hipGetLastError();
 }
 

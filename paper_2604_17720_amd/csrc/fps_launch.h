@@ -53,6 +53,9 @@ hipError_t launch_fill(int B, int N, int k, int R, int32_t *idx, long idx_stride
 // dst[b][j] = xyz[b][sel[b][j]] for j < S
 hipError_t launch_gather_points(const float *xyz, int B, int N, const int32_t *sel,
                                 long sel_stride, int S, float *dst, hipStream_t s);
+// out[b][j][0..C) = rows[b][sel[b][j]][0..C) for j < S
+hipError_t launch_gather_rows(const float *rows, int B, int N, int C, const int32_t *sel,
+                              long sel_stride, int S, float *out, hipStream_t s);
 // out[b][j] = prev[b][loc[b][j]] for j < S
 hipError_t launch_compose(const int32_t *prev, long prev_stride, const int32_t *loc,
                           long loc_stride, int B, int S, int32_t *out, long out_stride,

@@ -206,6 +206,24 @@ def test_stages_on_pruned_first_layer(fb, oracle, mode):
     assert np.array_equal(got, oracle.fps_stages(x, ms, mode, 1, 4, 3, 0))
 
 
+def test_gather_rows_of_stage_outputs(fb):
+    """Rows (coordinates or features) at the sampled indices, in sample order; pure
+    index work, so the check is an exact comparison with NumPy fancy indexing."""
+    import torch
+    x = inputs.make_config(3, B=3, N=5000)
+    feat = np.random.default_rng(5).standard_normal((3, 5000, 17)).astype(np.float32)
+    outs = fb.ffps_cached_stages(_dev(x), (1000, 250, 61), 0)
+    for o in outs:
+        sel = o.cpu().numpy()
+        got_xyz = fb.ffps_gather_rows(_dev(x), o).cpu().numpy()
+        got_feat = fb.ffps_gather_rows(_dev(feat), o).cpu().numpy()
+        for b in range(3):
+            assert np.array_equal(got_xyz[b], x[b][sel[b]])
+            assert np.array_equal(got_feat[b], feat[b][sel[b]])
+    with pytest.raises(ValueError):
+        fb.ffps_gather_rows(_dev(x), outs[0].to(torch.int64))
+
+
 # ------------------------------------------------- full benchmark sizes ----
 def _radius64(x, sel):
     """Coverage radius via a k-d tree in float64 (only ratios of it are used)."""
