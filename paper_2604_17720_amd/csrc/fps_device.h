@@ -73,27 +73,21 @@ __device__ __forceinline__ int readlane_i(int v, int lane) {
     return __builtin_amdgcn_readlane(v, lane);
 }
 
-// Element `sel` (wave-uniform) of a register array, read from lane `lane`
-// (wave-uniform).  The switch keeps the array in registers: each case names a
-// fixed element, and `sel` being uniform makes the branches scalar.
+// Coordinates of element `sel` of lane `lane` (both wave-uniform) of three
+// register arrays: a scalar jump picks the element, then three lane reads.
 template <int P>
-__device__ __forceinline__ float pick_elem(const float (&a)[P], int sel, int lane) {
-    float r = 0.f;
+__device__ __forceinline__ void pick_xyz(const float (&x)[P], const float (&y)[P],
+                                         const float (&z)[P], int sel, int lane, float &ox,
+                                         float &oy, float &oz) {
+    ox = oy = oz = 0.f;
 #pragma unroll
-    for (int j = 0; j < P; ++j)
-        if (sel == j) r = readlane_f(a[j], lane);
-    return r;
-}
-
-// --- 64-bit words exchanged between workgroups --------------------------------
-// Relaxed, device-scope, single-copy-atomic 64-bit accesses.  Each word carries
-// its own tag (upper half), so no fence is needed between words.
-__device__ __forceinline__ void store_word(uint64_t *p, uint32_t payload, uint32_t tag) {
-    __hip_atomic_store(p, ((uint64_t)tag << 32) | payload, __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint64_t load_word(const uint64_t *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int j = 0; j < P; ++j) {
+        if (sel == j) {
+            ox = readlane_f(x[j], lane);
+            oy = readlane_f(y[j], lane);
+            oz = readlane_f(z[j], lane);
+        }
+    }
 }
 
 }  // namespace ffps

@@ -104,23 +104,6 @@ __device__ __forceinline__ u32x4 lds_read16(uint32_t off) {
     return r;
 }
 
-// Coordinates of element `sel` of lane `lane` (both wave-uniform) of three
-// register arrays: a scalar jump picks the element, then three lane reads.
-template <int P>
-__device__ __forceinline__ void pick_xyz(const float (&x)[P], const float (&y)[P],
-                                         const float (&z)[P], int sel, int lane, float &ox,
-                                         float &oy, float &oz) {
-    ox = oy = oz = 0.f;
-#pragma unroll
-    for (int j = 0; j < P; ++j) {
-        if (sel == j) {
-            ox = readlane_f(x[j], lane);
-            oy = readlane_f(y[j], lane);
-            oz = readlane_f(z[j], lane);
-        }
-    }
-}
-
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return ~wave_max_u32(~v); }
 // Reductions over lanes 0..15 only (other lanes must pass the identity), wave-uniform.
 __device__ __forceinline__ uint32_t row_max_uniform(uint32_t v) {

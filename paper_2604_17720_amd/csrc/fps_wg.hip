@@ -77,9 +77,8 @@ __global__ __launch_bounds__(NT) void k_fps_wg(const float *__restrict__ xyz_all
         uint32_t wbits = wave_max_u32(f2u(bd));
         int wl = first_lane(f2u(bd) == wbits);
         int wj = readlane_i(bj, wl);
-        float wx = pick_elem<P>(x, wj, wl);
-        float wy = pick_elem<P>(y, wj, wl);
-        float wz = pick_elem<P>(z, wj, wl);
+        float wx, wy, wz;
+        pick_xyz<P>(x, y, z, wj, wl, wx, wy, wz);
         int widx = (wave * kWave + wl) * P + wj;
 
         if constexpr (NW == 1) {
