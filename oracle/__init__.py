@@ -19,6 +19,7 @@ _LIB = os.path.join(_HERE, "libfps_oracle.so")
 
 FLAG_CP = 1
 FLAG_IP = 2
+FLAG_PERM = 4
 MODE_CACHED = 0
 MODE_CHAIN = 1
 
@@ -49,10 +50,15 @@ def _load():
         lib.oracle_prune_sizes.restype = ci
         lib.oracle_candidates.argtypes = [ci, ci, ci, ip, ctypes.POINTER(ci)]
         lib.oracle_candidates.restype = ci
-        lib.oracle_fps_prune.argtypes = [fp, ci, ci, ci, ci, ci, ctypes.c_uint, ip, ctypes.POINTER(ci)]
+        lib.oracle_fps_prune.argtypes = [fp, ci, ci, ci, ci, ci, ctypes.c_uint, ctypes.c_uint64, ip,
+                                         ctypes.POINTER(ci)]
+        lib.oracle_perm.argtypes = [ctypes.c_int64, ctypes.c_uint64, ctypes.c_int64]
+        lib.oracle_perm.restype = ctypes.c_int64
+        lib.oracle_candidates_perm.argtypes = [ci, ci, ci, ctypes.c_uint64, ip, ctypes.POINTER(ci)]
+        lib.oracle_candidates_perm.restype = ci
         lib.oracle_fps_prune.restype = ci
         lib.oracle_fps_stages.argtypes = [fp, ci, ci, ctypes.POINTER(ci), ci, ci, ci,
-                                          ctypes.c_uint, ci, ip]
+                                          ctypes.c_uint, ctypes.c_uint64, ci, ip]
         lib.oracle_fps_stages.restype = ci
         lib.oracle_coverage_radius.argtypes = [fp, ci, ip, ci]
         lib.oracle_coverage_radius.restype = ctypes.c_double
@@ -121,36 +127,59 @@ def candidates(N, Nc, start=0):
     return cand, pos.value
 
 
-def _fps_prune1(xyz, M, keep_num, keep_den, flags=FLAG_CP | FLAG_IP, start=0):
+def perm(N, seed, j):
+    """Image of j under the seeded bijection of [0, N) (random select / fill)."""
+    return int(_load().oracle_perm(N, seed, j))
+
+
+def candidates_perm(N, Nc, start, seed):
+    cand = np.empty(Nc, dtype=np.int32)
+    pos = ctypes.c_int()
+    rc = _load().oracle_candidates_perm(N, Nc, start, seed, _iptr(cand), ctypes.byref(pos))
+    if rc:
+        raise ValueError("oracle_candidates_perm: invalid arguments")
+    return cand, pos.value
+
+
+def _fps_prune1(xyz, M, keep_num, keep_den, flags=FLAG_CP | FLAG_IP, start=0, seed=0):
     a = _cloud(xyz)
     idx = np.empty(M, dtype=np.int32)
     k = ctypes.c_int()
-    rc = _load().oracle_fps_prune(_fptr(a), a.shape[0], M, start, keep_num, keep_den, flags,
+    rc = _load().oracle_fps_prune(_fptr(a), a.shape[0], M, start, keep_num, keep_den, flags, seed,
                                   _iptr(idx), ctypes.byref(k))
     if rc:
         raise ValueError(f"oracle_fps_prune: invalid arguments (rc={rc})")
     return idx
 
 
-def fps_prune(xyz, M, keep_num, keep_den, flags=FLAG_CP | FLAG_IP, start=0):
-    """FPS-Prune (Alg. 1, layer 1).  First k entries are FPS order, then the fill."""
-    return _batched(_fps_prune1, xyz, M, keep_num, keep_den, flags, start)
+def fps_prune(xyz, M, keep_num, keep_den, flags=FLAG_CP | FLAG_IP, start=0, seed=0):
+    """FPS-Prune (Alg. 1, layer 1).  First k entries are FPS order, then the fill.
+    With FLAG_PERM cloud b of a batch uses seed + b."""
+    a = np.asarray(xyz)
+    if a.ndim == 3:
+        return np.stack([_fps_prune1(a[b], M, keep_num, keep_den, flags, start, seed + b)
+                         for b in range(a.shape[0])])
+    return _fps_prune1(a, M, keep_num, keep_den, flags, start, seed)
 
 
-def _fps_stages1(xyz, Ms, mode, keep_num=1, keep_den=1, flags=0, start=0):
+def _fps_stages1(xyz, Ms, mode, keep_num=1, keep_den=1, flags=0, start=0, seed=0):
     a = _cloud(xyz)
     ms = (ctypes.c_int * len(Ms))(*[int(m) for m in Ms])
     out = np.empty(int(sum(Ms)), dtype=np.int32)
     rc = _load().oracle_fps_stages(_fptr(a), a.shape[0], len(Ms), ms, start, keep_num, keep_den,
-                                   flags, mode, _iptr(out))
+                                   flags, seed, mode, _iptr(out))
     if rc:
         raise ValueError(f"oracle_fps_stages: invalid arguments (rc={rc})")
     return out
 
 
-def fps_stages(xyz, Ms, mode, keep_num=1, keep_den=1, flags=0, start=0):
+def fps_stages(xyz, Ms, mode, keep_num=1, keep_den=1, flags=0, start=0, seed=0):
     """Stage chain (Alg. 1 / Sec. 3.3); returns the layers back to back."""
-    return _batched(_fps_stages1, xyz, Ms, mode, keep_num, keep_den, flags, start)
+    a = np.asarray(xyz)
+    if a.ndim == 3:
+        return np.stack([_fps_stages1(a[b], Ms, mode, keep_num, keep_den, flags, start, seed + b)
+                         for b in range(a.shape[0])])
+    return _fps_stages1(a, Ms, mode, keep_num, keep_den, flags, start, seed)
 
 
 def coverage_radius(xyz, sel):

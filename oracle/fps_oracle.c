@@ -34,6 +34,7 @@
 
 #define ORACLE_FLAG_CP 1u /* candidate pruning  (Alg. 1, step "P' <- UniformSample") */
 #define ORACLE_FLAG_IP 2u /* iteration pruning  (Alg. 1, step "k <- (1-p) M1")       */
+#define ORACLE_FLAG_PERM 4u /* seeded random sub-sample and fill instead of strided ones */
 
 #define ORACLE_MODE_CACHED 0      /* Alg. 1, layers 2..L: prefixes of the cached P1 */
 #define ORACLE_MODE_CHAIN 1       /* Sec. 3.3: every layer runs its own FPS          */
@@ -113,6 +114,8 @@ int oracle_prune_sizes(int N, int M, int keep_num, int keep_den, unsigned flags,
 {
     if (N < 1 || M < 1 || M > N || keep_num < 1 || keep_den < 1 || keep_num > keep_den)
         return -1;
+    if (flags & ~(ORACLE_FLAG_CP | ORACLE_FLAG_IP | ORACLE_FLAG_PERM))
+        return -1;
     int64_t nc = (flags & ORACLE_FLAG_CP) ? ceil_frac(N, keep_num, keep_den) : N;
     int64_t kk = (flags & ORACLE_FLAG_IP) ? ceil_frac(M, keep_num, keep_den) : M;
     if (kk < 1 || kk > nc)
@@ -150,14 +153,85 @@ int oracle_candidates(int N, int Nc, int start, int32_t *cand, int *start_pos)
 }
 
 /*
+ * Seeded bijection of [0, N) for the random variants of "UniformSample" and
+ * "RandomSample" (Alg. 1, layer 1), which the paper leaves unspecified.
+ * A 4-round Feistel network over 2h bits, 2^(2h) >= N, with a 32-bit integer
+ * mixer as round function, walked until the value falls below N (a cycle walk
+ * of a bijection of a superset is a bijection of the subset).  Stateless:
+ * element j is computed on its own, so a parallel implementation needs no
+ * sequential random stream.
+ */
+static uint32_t perm_mix(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x85EBCA6Bu;
+    x ^= x >> 13;
+    x *= 0xC2B2AE35u;
+    x ^= x >> 16;
+    return x;
+}
+
+int64_t oracle_perm(int64_t N, uint64_t seed, int64_t j)
+{
+    if (N < 1 || j < 0 || j >= N)
+        return -1;
+    int h = 1;
+    while (((int64_t)1 << (2 * h)) < N)
+        ++h;
+    const uint32_t mask = ((uint32_t)1 << h) - 1u;
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint64_t x = (uint64_t)j;
+    do {
+        uint32_t l = (uint32_t)(x >> h) & mask, r = (uint32_t)x & mask;
+        for (uint32_t round = 0; round < 4; ++round) {
+            uint32_t f = perm_mix(r ^ (key[round & 1] + 0x9E3779B9u * (round + 1))) & mask;
+            uint32_t t = l ^ f;
+            l = r;
+            r = t;
+        }
+        x = ((uint64_t)l << h) | r;
+    } while (x >= (uint64_t)N);
+    return (int64_t)x;
+}
+
+/*
+ * Random candidate list: the N' images perm(j), j < N', with perm(N'-1)
+ * replaced by `start` when start is not among them; ascending order.
+ */
+int oracle_candidates_perm(int N, int Nc, int start, uint64_t seed, int32_t *cand, int *start_pos)
+{
+    if (N < 1 || Nc < 1 || Nc > N || start < 0 || start >= N)
+        return -1;
+    int has = 0;
+    for (int j = 0; j < Nc; ++j) {
+        cand[j] = (int32_t)oracle_perm(N, seed, j);
+        if (cand[j] == start)
+            has = 1;
+    }
+    if (!has)
+        cand[Nc - 1] = start;
+    qsort(cand, (size_t)Nc, sizeof(int32_t), cmp_i32);
+    *start_pos = -1;
+    for (int j = 0; j < Nc; ++j)
+        if (cand[j] == start)
+            *start_pos = j;
+    return *start_pos < 0 ? -1 : 0;
+}
+
+/* second, independent permutation for the fill */
+#define ORACLE_FILL_SEED_XOR 0xD1B54A32D192ED03ull
+
+/*
  * FPS-Prune (Alg. 1, layer 1).  idx[0..k-1] = FPS order on the candidate
  * cloud mapped back to indices of the full cloud; idx[k..M-1] = fill picks:
  * with free = ascending list of the N - k indices not picked by FPS,
  *   fill[j] = free[ floor(j * (N - k) / R) ],  j = 0..R-1.
  * The fill is drawn from the full cloud, not from the candidate cloud.
+ * With ORACLE_FLAG_PERM both the candidate list and the fill are seeded random
+ * draws instead (oracle_candidates_perm; fill as described in the body).
  */
 int oracle_fps_prune(const float *xyz, int N, int M, int start, int keep_num, int keep_den,
-                     unsigned flags, int32_t *idx, int *k_out)
+                     unsigned flags, uint64_t seed, int32_t *idx, int *k_out)
 {
     int Nc, k, R;
     if (!xyz || !idx || start < 0 || start >= N)
@@ -172,7 +246,8 @@ int oracle_fps_prune(const float *xyz, int N, int M, int start, int keep_num, in
     int rc = -2, spos = 0;
     if (!cand || !cxyz || !loc || !taken || !freelist)
         goto done;
-    if (oracle_candidates(N, Nc, start, cand, &spos)) {
+    if ((flags & ORACLE_FLAG_PERM) ? oracle_candidates_perm(N, Nc, start, seed, cand, &spos)
+                                   : oracle_candidates(N, Nc, start, cand, &spos)) {
         rc = -1;
         goto done;
     }
@@ -185,7 +260,16 @@ int oracle_fps_prune(const float *xyz, int N, int M, int start, int keep_num, in
         idx[j] = cand[loc[j]];
         taken[idx[j]] = 1;
     }
-    {
+    if (flags & ORACLE_FLAG_PERM) {
+        /* random fill: walk a second permutation of [0, N) and keep the first R
+         * indices that FPS did not pick, in that order */
+        int got = 0;
+        for (int64_t j = 0; j < N && got < R; ++j) {
+            int32_t t = (int32_t)oracle_perm(N, seed ^ ORACLE_FILL_SEED_XOR, j);
+            if (!taken[t])
+                idx[k + got++] = t;
+        }
+    } else {
         int64_t nfree = 0;
         for (int i = 0; i < N; ++i)
             if (!taken[i])
@@ -215,14 +299,14 @@ done:
  * out holds the layers back to back: layer l at offset Ms[0] + ... + Ms[l-1].
  */
 int oracle_fps_stages(const float *xyz, int N, int L, const int *Ms, int start, int keep_num,
-                      int keep_den, unsigned flags, int mode, int32_t *out)
+                      int keep_den, unsigned flags, uint64_t seed, int mode, int32_t *out)
 {
     if (!xyz || !Ms || !out || L < 1)
         return -1;
     for (int l = 1; l < L; ++l)
         if (Ms[l] > Ms[l - 1] || Ms[l] < 1)
             return -1;
-    int rc = oracle_fps_prune(xyz, N, Ms[0], start, keep_num, keep_den, flags, out, NULL);
+    int rc = oracle_fps_prune(xyz, N, Ms[0], start, keep_num, keep_den, flags, seed, out, NULL);
     if (rc)
         return rc;
     size_t off = (size_t)Ms[0];

@@ -318,3 +318,64 @@ def test_coverage_ratio_lower_bound(oracle):
             assert 0.5 <= rho < 4.0
     stages = oracle.fps_stages(x, (2000, 500), oracle.MODE_CACHED)
     assert oracle.coverage_radius(x, stages[2000:]) == oracle.coverage_radius(x, exact[:500])
+
+
+# --------------------------------------------------------------------------
+# seeded random select / fill (the literal "UniformSample" / "RandomSample" of
+# Alg. 1, which the paper leaves unspecified)
+# --------------------------------------------------------------------------
+def test_perm_is_a_bijection_for_every_size_and_seed(oracle):
+    for n in (1, 2, 3, 4, 5, 16, 17, 63, 64, 65, 1000, 4096, 4097, 20011):
+        for seed in (0, 1, 2 ** 32, 2 ** 64 - 1, 0x0123456789ABCDEF):
+            img = [oracle.perm(n, seed, j) for j in range(n)]
+            assert sorted(img) == list(range(n)), (n, seed)
+
+
+def test_perm_depends_on_the_seed_and_spreads_uniformly(oracle):
+    n, nc, seeds = 60, 12, 600
+    hits = np.zeros(n)
+    first = set()
+    for seed in range(seeds):
+        img = [oracle.perm(n, seed, j) for j in range(nc)]
+        first.add(tuple(img[:4]))
+        hits[img] += 1
+    assert len(first) > 0.9 * seeds                       # seeds give different draws
+    expect = seeds * nc / n                               # each index equally likely
+    assert np.all(np.abs(hits - expect) < 5 * np.sqrt(expect))
+    # both 32-bit halves of the seed matter
+    a = [oracle.perm(1000, 5, j) for j in range(50)]
+    assert a != [oracle.perm(1000, 5 + 2 ** 32, j) for j in range(50)]
+    assert a != [oracle.perm(1000, 6, j) for j in range(50)]
+
+
+@pytest.mark.parametrize("kn,kd", [(1, 4), (2, 3)])
+@pytest.mark.parametrize("flags", [1 | 4, 2 | 4, 3 | 4])
+def test_random_prune_structure(oracle, kn, kd, flags):
+    """Semantics of the random variant, rebuilt with Python sets from the
+    permutation alone: candidates = images of the first N' arguments (with the
+    seed point forced in), ascending; fill = first R images of a second
+    permutation that FPS did not pick, in that order."""
+    x = inputs.make_config(4, N=2003)[0]
+    n, m, start, seed = 2003, 500, 77, 99
+    nc, k, r = oracle.prune_sizes(n, m, kn, kd, flags)
+    got = oracle.fps_prune(x, m, kn, kd, flags, start, seed).tolist()
+    img = [oracle.perm(n, seed, j) for j in range(nc)]
+    if start not in img:
+        img[-1] = start
+    cand = sorted(img)
+    c2, pos = oracle.candidates_perm(n, nc, start, seed)
+    assert c2.tolist() == cand and cand[pos] == start and len(set(cand)) == nc
+    loc = oracle.fps_exact(x[cand], k, cand.index(start))
+    assert got[:k] == [cand[j] for j in loc]
+    picked = set(got[:k])
+    fill = []
+    j = 0
+    while len(fill) < r:
+        t = oracle.perm(n, seed ^ 0xD1B54A32D192ED03, j)
+        if t not in picked:
+            fill.append(t)
+        j += 1
+    assert got[k:] == fill
+    assert len(set(got)) == m
+    # keep = 1/1 is still standard FPS (Sec. 3.2), whatever the seed
+    assert np.array_equal(oracle.fps_prune(x, m, 1, 1, flags, start, seed), oracle.fps_exact(x, m, start))
