@@ -48,6 +48,7 @@ extern "C" {
 /* FPS-Prune switches (Alg. 1, layer 1). */
 #define FFPS_FLAG_CP 1u /* candidate pruning: FPS sees only N' = ceil(N * keep) points      */
 #define FFPS_FLAG_IP 2u /* iteration pruning: FPS stops after k = ceil(M * keep) picks       */
+#define FFPS_FLAG_PERM 4u /* seeded random sub-sample and fill instead of the strided ones    */
 
 /* How layers 2..L of a stage chain are produced. */
 #define FFPS_MODE_CACHED 0 /* FPS-Cache: prefixes of layer 1 (Alg. 1, layers 2..L)           */
@@ -115,15 +116,30 @@ int ffps_exact(const float *d_xyz, int B, int N, int M, int start_idx, int varia
  *               (drawn from the full cloud, not from the candidates).
  * keep = 1/1 (p = 0) gives exactly ffps_exact.  k_out_host (may be NULL)
  * receives k.  Other arguments as ffps_exact.
+ *
+ * With FFPS_FLAG_PERM the two deterministic strided rules are replaced by the
+ * literal random draws of Alg. 1, made reproducible by `seed` (cloud b uses
+ * seed + b).  Let perm_s be the seeded bijection of [0, N): a 4-round Feistel
+ * network over 2h bits (2^(2h) >= N, h >= 1) on the halves (l, r) of the argument,
+ *   f = mix(r ^ (key[round & 1] + 0x9E3779B9 * (round + 1))) & (2^h - 1),
+ *   (l, r) <- (r, l ^ f),   key = {low, high 32 bits of s},
+ *   mix(x): x ^= x >> 16; x *= 0x85EBCA6B; x ^= x >> 13; x *= 0xC2B2AE35; x ^= x >> 16,
+ * repeated until the value is below N.  Then
+ *   candidates  sort{ perm_seed(j) : j < N' }, with perm_seed(N'-1) replaced by
+ *               start_idx when start_idx is not among them;
+ *   fill part   the first R values of perm_(seed ^ 0xD1B54A32D192ED03)(0), (1), ...
+ *               that the FPS part did not pick, in that order.
+ * `seed` is ignored without FFPS_FLAG_PERM.
  */
 int ffps_prune(const float *d_xyz, int B, int N, int M, int start_idx, int keep_num,
-               int keep_den, unsigned flags, int variant, int32_t *d_idx, int *k_out_host,
-               void *d_ws, size_t ws_bytes, void *stream);
+               int keep_den, unsigned flags, uint64_t seed, int variant, int32_t *d_idx,
+               int *k_out_host, void *d_ws, size_t ws_bytes, void *stream);
 
 /*
  * Hierarchical stage chain (Alg. 1; Sec. 3.3).
  *   L, M_stages  host array of L sample counts, N >= M_stages[0] >= ... >= M_stages[L-1] >= 1
- *   layer 1      ffps_prune with M = M_stages[0] (exact FPS when keep = 1/1)
+ *   layer 1      ffps_prune with M = M_stages[0] and the same keep, flags, seed
+ *                (exact FPS when keep = 1/1)
  *   FFPS_MODE_CACHED  layer l = first M_stages[l] entries of layer 1
  *   FFPS_MODE_CHAIN   layer l = exact FPS over the points of layer l-1 taken in
  *                     sample order, started at its first point, M_stages[l]
@@ -133,8 +149,9 @@ int ffps_prune(const float *d_xyz, int B, int N, int M, int start_idx, int keep_
  *   d_ws         workspace of ws_bytes >= ffps_workspace_bytes(B, N, M_stages[0])
  */
 int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_stages,
-                       int start_idx, int keep_num, int keep_den, unsigned flags, int mode,
-                       int variant, int32_t *d_idx, void *d_ws, size_t ws_bytes, void *stream);
+                       int start_idx, int keep_num, int keep_den, unsigned flags, uint64_t seed,
+                       int mode, int variant, int32_t *d_idx, void *d_ws, size_t ws_bytes,
+                       void *stream);
 
 /*
  * What the layer after a sampling stage consumes (Sec. 1: each stage samples,

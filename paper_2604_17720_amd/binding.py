@@ -20,6 +20,7 @@ FFPS_ERR_TIMEOUT = -5
 FFPS_ERR_UNSUPPORTED_SIZE = -6
 FFPS_FLAG_CP = 1
 FFPS_FLAG_IP = 2
+FFPS_FLAG_PERM = 4
 FFPS_MODE_CACHED = 0
 FFPS_MODE_CHAIN = 1
 FFPS_VARIANT_AUTO = 0
@@ -65,9 +66,10 @@ def lib() -> ctypes.CDLL:
         L.ffps_workspace_bytes.argtypes = [c_int, c_int, c_int, ctypes.POINTER(c_sz)]
         L.ffps_exact.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_sz, c_vp]
         L.ffps_prune.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, ctypes.c_uint,
-                                 c_int, c_vp, ip, c_vp, c_sz, c_vp]
+                                 ctypes.c_uint64, c_int, c_vp, ip, c_vp, c_sz, c_vp]
         L.ffps_cached_stages.argtypes = [c_vp, c_int, c_int, c_int, ip, c_int, c_int, c_int,
-                                         ctypes.c_uint, c_int, c_int, c_vp, c_vp, c_sz, c_vp]
+                                         ctypes.c_uint, ctypes.c_uint64, c_int, c_int, c_vp, c_vp,
+                                         c_sz, c_vp]
         L.ffps_last_status.argtypes = [c_vp, c_vp]
         L.ffps_last_rounds.argtypes = [c_vp, c_vp]
         L.ffps_gather_rows.argtypes = [c_vp, c_int, c_int, c_int, c_vp, ctypes.c_long, c_int, c_vp, c_vp]
@@ -154,7 +156,7 @@ def ffps_exact(xyz, M, start_idx=0, variant=FFPS_VARIANT_AUTO, return_maxdist=Fa
 
 
 def ffps_prune(xyz, M, keep_num, keep_den, flags=FFPS_FLAG_CP | FFPS_FLAG_IP, start_idx=0,
-               variant=FFPS_VARIANT_AUTO, workspace=None, stream=None, out=None):
+               variant=FFPS_VARIANT_AUTO, workspace=None, stream=None, out=None, seed=0):
     """FPS-Prune.  Returns (idx int32 [B,M], k): idx[:, :k] is FPS order, idx[:, k:] the fill."""
     torch, x, B, N = _prep(xyz)
     if not (1 <= M <= N):
@@ -162,7 +164,7 @@ def ffps_prune(xyz, M, keep_num, keep_den, flags=FFPS_FLAG_CP | FFPS_FLAG_IP, st
     ws = make_workspace(B, N, M, x.device) if workspace is None else workspace
     idx = torch.empty((B, M), dtype=torch.int32, device=x.device) if out is None else out
     k = ctypes.c_int()
-    rc = lib().ffps_prune(x.data_ptr(), B, N, M, start_idx, keep_num, keep_den, flags, variant,
+    rc = lib().ffps_prune(x.data_ptr(), B, N, M, start_idx, keep_num, keep_den, flags, seed, variant,
                           idx.data_ptr(), ctypes.byref(k), ws.data_ptr(), ws.numel(),
                           _stream(torch, stream))
     if rc:
@@ -172,7 +174,7 @@ def ffps_prune(xyz, M, keep_num, keep_den, flags=FFPS_FLAG_CP | FFPS_FLAG_IP, st
 
 def ffps_cached_stages(xyz, M_stages, mode=FFPS_MODE_CACHED, keep_num=1, keep_den=1, flags=0,
                        start_idx=0, variant=FFPS_VARIANT_AUTO, workspace=None, stream=None,
-                       out=None):
+                       out=None, seed=0):
     """Stage chain.  Returns a list of int32 [B,M_l] views, one per layer, of one
     [B, sum(M_stages)] tensor."""
     torch, x, B, N = _prep(xyz)
@@ -184,7 +186,7 @@ def ffps_cached_stages(xyz, M_stages, mode=FFPS_MODE_CACHED, keep_num=1, keep_de
     idx = torch.empty((B, S), dtype=torch.int32, device=x.device) if out is None else out
     arr = (ctypes.c_int * len(ms))(*ms)
     rc = lib().ffps_cached_stages(x.data_ptr(), B, N, len(ms), arr, start_idx, keep_num, keep_den,
-                                  flags, mode, variant, idx.data_ptr(), ws.data_ptr(), ws.numel(),
+                                  flags, seed, mode, variant, idx.data_ptr(), ws.data_ptr(), ws.numel(),
                                   _stream(torch, stream))
     if rc:
         raise FlashFPSError(rc, "ffps_cached_stages")

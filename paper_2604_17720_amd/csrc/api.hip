@@ -15,7 +15,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Workspace {  // byte offsets into the caller's workspace
-    size_t status, exchange, cxyz, loc, bitmap, mind, total;
+    size_t status, exchange, cxyz, loc, bitmap, mind, cand, spos, total;
 };
 
 Workspace carve(int B, int N, int M) {
@@ -27,6 +27,8 @@ Workspace carve(int B, int N, int M) {
     w.loc = o;      o += align_up((size_t)B * M * sizeof(int32_t));
     w.bitmap = o;   o += align_up((size_t)B * ((N + 31) / 32) * sizeof(uint32_t));
     w.mind = o;     o += align_up((size_t)B * N * sizeof(float));
+    w.cand = o;     o += align_up((size_t)B * N * sizeof(int32_t));
+    w.spos = o;     o += align_up((size_t)B * sizeof(int));
     w.total = o;
     return w;
 }
@@ -107,13 +109,13 @@ int resolve_variant(int B, int N, int variant, const Device &dev) {
 
 // Exact FPS of B clouds [N] into idx (row stride idx_stride).  Arguments are
 // already validated.
-int run_exact(const float *xyz, int B, int N, int M, int start, int variant, int32_t *idx,
-              long idx_stride, float *md, long md_stride, char *ws, const Workspace &w,
-              const Device &dev, hipStream_t s) {
+int run_exact(const float *xyz, int B, int N, int M, int start, const int *start_dev, int variant,
+              int32_t *idx, long idx_stride, float *md, long md_stride, char *ws,
+              const Workspace &w, const Device &dev, hipStream_t s) {
     int v = resolve_variant(B, N, variant, dev);
     if (v < 0) return v;
     if (v == FFPS_VARIANT_WG)
-        return hip_rc(launch_fps_wg(xyz, B, N, M, start, idx, idx_stride, md, md_stride, s));
+        return hip_rc(launch_fps_wg(xyz, B, N, M, start, start_dev, idx, idx_stride, md, md_stride, s));
     if (v == FFPS_VARIANT_GRID) {
         const GridPlan plan = plan_fps_grid(B, N, dev.num_cu);
         for (int b = 0; b < B; b += plan.clouds_per_launch) {
@@ -121,6 +123,7 @@ int run_exact(const float *xyz, int B, int N, int M, int start, int variant, int
             int rc = clear_exchange(ws, w, clouds, s);
             if (rc) return rc;
             hipError_t e = launch_fps_grid(xyz + (size_t)b * N * 3, clouds, N, M, start,
+                                           start_dev ? start_dev + b : nullptr,
                                            idx + b * idx_stride, idx_stride,
                                            md ? md + b * md_stride : nullptr, md_stride,
                                            ws + w.exchange, (int *)(ws + w.status),
@@ -134,7 +137,8 @@ int run_exact(const float *xyz, int B, int N, int M, int start, int variant, int
             int rc = clear_exchange(ws, w, 1, s);
             if (rc) return rc;
             hipError_t e = launch_fps_stream(xyz + (size_t)b * N * 3, (float *)(ws + w.mind) + (size_t)b * N,
-                                             N, M, start, idx + b * idx_stride,
+                                             N, M, start, start_dev ? start_dev + b : nullptr,
+                                             idx + b * idx_stride,
                                              md ? md + b * md_stride : nullptr, ws + w.exchange,
                                              (int *)(ws + w.status), dev.num_cu,
                                              variant_picks(variant), s);
@@ -146,28 +150,41 @@ int run_exact(const float *xyz, int B, int N, int M, int start, int variant, int
 }
 
 int run_prune(const float *xyz, int B, int N, int M, int start, int keep_num, int keep_den,
-              unsigned flags, int variant, int32_t *idx, long idx_stride, char *ws,
+              unsigned flags, uint64_t seed, int variant, int32_t *idx, long idx_stride, char *ws,
               const Workspace &w, const Device &dev, hipStream_t s) {
     int Nc, k, R;
     int rc = ffps_prune_sizes(N, M, keep_num, keep_den, flags, &Nc, &k, &R);
     if (rc) return rc;
+    const bool perm = (flags & FFPS_FLAG_PERM) != 0;
+    uint32_t *bitmap = (uint32_t *)(ws + w.bitmap);
     if (Nc < N) {
         float *cxyz = (float *)(ws + w.cxyz);
         int32_t *loc = (int32_t *)(ws + w.loc);
-        rc = hip_rc(launch_gather_candidates(xyz, B, N, Nc, start, cxyz, s));
-        if (rc) return rc;
-        long j0 = (((long)N - start) * Nc + N - 1) / N;  // where the strided list wraps
-        if (j0 > Nc) j0 = Nc;
-        int spos = (int)((Nc - j0) % Nc);  // position of start_idx in the sorted list
-        rc = run_exact(cxyz, B, Nc, k, spos, variant, loc, k, nullptr, 0, ws, w, dev, s);
-        if (rc) return rc;
-        rc = hip_rc(launch_map_candidates(loc, k, B, N, Nc, start, k, idx, idx_stride, s));
+        if (perm) {
+            int32_t *cand = (int32_t *)(ws + w.cand);
+            int *spos = (int *)(ws + w.spos);
+            rc = hip_rc(launch_perm_candidates(xyz, B, N, Nc, start, seed, bitmap, cand, cxyz, spos, s));
+            if (rc) return rc;
+            rc = run_exact(cxyz, B, Nc, k, 0, spos, variant, loc, k, nullptr, 0, ws, w, dev, s);
+            if (rc) return rc;
+            rc = hip_rc(launch_compose(cand, Nc, loc, k, B, k, idx, idx_stride, s));
+        } else {
+            rc = hip_rc(launch_gather_candidates(xyz, B, N, Nc, start, cxyz, s));
+            if (rc) return rc;
+            long j0 = (((long)N - start) * Nc + N - 1) / N;  // where the strided list wraps
+            if (j0 > Nc) j0 = Nc;
+            int spos = (int)((Nc - j0) % Nc);  // position of start_idx in the sorted list
+            rc = run_exact(cxyz, B, Nc, k, spos, nullptr, variant, loc, k, nullptr, 0, ws, w, dev, s);
+            if (rc) return rc;
+            rc = hip_rc(launch_map_candidates(loc, k, B, N, Nc, start, k, idx, idx_stride, s));
+        }
         if (rc) return rc;
     } else {
-        rc = run_exact(xyz, B, N, k, start, variant, idx, idx_stride, nullptr, 0, ws, w, dev, s);
+        rc = run_exact(xyz, B, N, k, start, nullptr, variant, idx, idx_stride, nullptr, 0, ws, w, dev, s);
         if (rc) return rc;
     }
-    return hip_rc(launch_fill(B, N, k, R, idx, idx_stride, (uint32_t *)(ws + w.bitmap), s));
+    if (perm) return hip_rc(launch_fill_perm(B, N, k, R, seed, idx, idx_stride, bitmap, s));
+    return hip_rc(launch_fill(B, N, k, R, idx, idx_stride, bitmap, s));
 }
 
 }  // namespace
@@ -194,7 +211,7 @@ int ffps_prune_sizes(int N, int M, int keep_num, int keep_den, unsigned flags, i
     if (!Nc || !k || !R) return FFPS_ERR_INVALID_ARG;
     if (N < 1 || M < 1 || M > N) return FFPS_ERR_INVALID_ARG;
     if (keep_num < 1 || keep_den < 1 || keep_num > keep_den) return FFPS_ERR_INVALID_ARG;
-    if (flags & ~(FFPS_FLAG_CP | FFPS_FLAG_IP)) return FFPS_ERR_INVALID_ARG;
+    if (flags & ~(FFPS_FLAG_CP | FFPS_FLAG_IP | FFPS_FLAG_PERM)) return FFPS_ERR_INVALID_ARG;
     long nc = (flags & FFPS_FLAG_CP) ? ((long)N * keep_num + keep_den - 1) / keep_den : N;
     long kk = (flags & FFPS_FLAG_IP) ? ((long)M * keep_num + keep_den - 1) / keep_den : M;
     if (kk < 1 || kk > nc) return FFPS_ERR_INVALID_ARG;
@@ -223,13 +240,13 @@ int ffps_exact(const float *d_xyz, int B, int N, int M, int start_idx, int varia
     if ((rc = resolve_variant(B, N, variant, dev)) < 0) return rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = clear_status((char *)d_ws, w, s))) return rc;
-    return run_exact(d_xyz, B, N, M, start_idx, variant, d_idx, M, d_maxdist, M, (char *)d_ws, w,
-                     dev, s);
+    return run_exact(d_xyz, B, N, M, start_idx, nullptr, variant, d_idx, M, d_maxdist, M,
+                     (char *)d_ws, w, dev, s);
 }
 
 int ffps_prune(const float *d_xyz, int B, int N, int M, int start_idx, int keep_num, int keep_den,
-               unsigned flags, int variant, int32_t *d_idx, int *k_out_host, void *d_ws,
-               size_t ws_bytes, void *stream) {
+               unsigned flags, uint64_t seed, int variant, int32_t *d_idx, int *k_out_host,
+               void *d_ws, size_t ws_bytes, void *stream) {
     int rc = check_common(d_xyz, B, N, M, start_idx, d_idx, d_ws);
     if (rc) return rc;
     if ((rc = check_variant(variant))) return rc;
@@ -243,13 +260,13 @@ int ffps_prune(const float *d_xyz, int B, int N, int M, int start_idx, int keep_
     hipStream_t s = (hipStream_t)stream;
     if ((rc = clear_status((char *)d_ws, w, s))) return rc;
     if (k_out_host) *k_out_host = k;
-    return run_prune(d_xyz, B, N, M, start_idx, keep_num, keep_den, flags, variant, d_idx, M,
+    return run_prune(d_xyz, B, N, M, start_idx, keep_num, keep_den, flags, seed, variant, d_idx, M,
                      (char *)d_ws, w, dev, s);
 }
 
 int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_stages, int start_idx,
-                       int keep_num, int keep_den, unsigned flags, int mode, int variant,
-                       int32_t *d_idx, void *d_ws, size_t ws_bytes, void *stream) {
+                       int keep_num, int keep_den, unsigned flags, uint64_t seed, int mode,
+                       int variant, int32_t *d_idx, void *d_ws, size_t ws_bytes, void *stream) {
     if (!M_stages || L < 1) return FFPS_ERR_INVALID_ARG;
     int rc = check_common(d_xyz, B, N, M_stages[0], start_idx, d_idx, d_ws);
     if (rc) return rc;
@@ -271,8 +288,8 @@ int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_sta
     char *ws = (char *)d_ws;
     if ((rc = clear_status(ws, w, s))) return rc;
 
-    rc = run_prune(d_xyz, B, N, M_stages[0], start_idx, keep_num, keep_den, flags, variant, d_idx, S,
-                   ws, w, dev, s);
+    rc = run_prune(d_xyz, B, N, M_stages[0], start_idx, keep_num, keep_den, flags, seed, variant,
+                   d_idx, S, ws, w, dev, s);
     if (rc) return rc;
     long off = M_stages[0];
     const int32_t *prev = d_idx;
@@ -285,8 +302,8 @@ int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_sta
             int32_t *loc = (int32_t *)(ws + w.loc);
             rc = hip_rc(launch_gather_points(d_xyz, B, N, prev, S, M_stages[l - 1], pxyz, s));
             if (rc) return rc;
-            rc = run_exact(pxyz, B, M_stages[l - 1], M_stages[l], 0, variant, loc, M_stages[l],
-                           nullptr, 0, ws, w, dev, s);
+            rc = run_exact(pxyz, B, M_stages[l - 1], M_stages[l], 0, nullptr, variant, loc,
+                           M_stages[l], nullptr, 0, ws, w, dev, s);
             if (rc) return rc;
             rc = hip_rc(launch_compose(prev, S, loc, M_stages[l], B, M_stages[l], cur, S, s));
         }

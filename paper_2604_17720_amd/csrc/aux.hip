@@ -159,6 +159,152 @@ __global__ void k_copy_prefix(const int32_t *__restrict__ src, long src_stride, 
         out[b * out_stride + j] = src[b * src_stride + j];
 }
 
+// ---- seeded random select / fill --------------------------------------------
+// Seeded bijection of [0, N): a 4-round Feistel network over 2h bits,
+// 2^(2h) >= N, with a 32-bit integer mixer as round function, walked until the
+// value falls below N.  Stateless: every element is computed on its own.
+struct Perm {
+    uint32_t n, mask, k0, k1;
+    int h;
+};
+__host__ __device__ inline Perm make_perm(int N, uint64_t seed) {
+    Perm p;
+    p.n = (uint32_t)N;
+    p.h = 1;
+    while ((1ull << (2 * p.h)) < (unsigned long long)N) ++p.h;
+    p.mask = (1u << p.h) - 1u;
+    p.k0 = (uint32_t)seed;
+    p.k1 = (uint32_t)(seed >> 32);
+    return p;
+}
+__device__ __forceinline__ uint32_t perm_mix(uint32_t x) {
+    x ^= x >> 16;
+    x *= 0x85EBCA6Bu;
+    x ^= x >> 13;
+    x *= 0xC2B2AE35u;
+    x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ uint32_t perm_at(const Perm &p, uint32_t j) {
+    uint32_t x = j;
+    do {
+        uint32_t l = (x >> p.h) & p.mask, r = x & p.mask;
+#pragma unroll
+        for (uint32_t round = 0; round < 4; ++round) {
+            uint32_t f = perm_mix(r ^ (((round & 1) ? p.k1 : p.k0) + 0x9E3779B9u * (round + 1))) & p.mask;
+            uint32_t t = l ^ f;
+            l = r;
+            r = t;
+        }
+        x = (l << p.h) | r;
+    } while (x >= p.n);
+    return x;
+}
+constexpr uint64_t kFillSeedXor = 0xD1B54A32D192ED03ull;
+
+// bitmap[b] |= { perm_{seed+b}(j) : j < Nc }   (bitmap cleared beforehand)
+__global__ void k_perm_mark(int N, int Nc, uint64_t seed, uint32_t *__restrict__ bitmap_all) {
+    const int b = blockIdx.y;
+    uint32_t *bm = bitmap_all + (size_t)b * ((N + 31) / 32);
+    const Perm p = make_perm(N, seed + (uint64_t)b);
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < Nc; j += gridDim.x * blockDim.x) {
+        uint32_t t = perm_at(p, (uint32_t)j);
+        atomicOr(&bm[t >> 5], 1u << (t & 31));
+    }
+}
+
+// One workgroup per cloud: force `start` into the candidate set (in place of
+// the last drawn candidate), then list the set in ascending order with the
+// candidates' coordinates, and report the position of `start` in it.
+__global__ __launch_bounds__(1024) void k_perm_compact(const float *__restrict__ xyz_all, int N, int Nc,
+                                                       int start, uint64_t seed,
+                                                       uint32_t *__restrict__ bitmap_all,
+                                                       int32_t *__restrict__ cand_all,
+                                                       float *__restrict__ cxyz_all,
+                                                       int *__restrict__ spos_all) {
+    __shared__ int part[1024];
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int words = (N + 31) / 32;
+    uint32_t *bm = bitmap_all + (size_t)b * words;
+    const float *xyz = xyz_all + (size_t)b * N * 3;
+    int32_t *cand = cand_all + (size_t)b * Nc;
+    float *cxyz = cxyz_all + (size_t)b * Nc * 3;
+    if (tid == 0 && !((bm[start >> 5] >> (start & 31)) & 1u)) {
+        const uint32_t last = perm_at(make_perm(N, seed + (uint64_t)b), (uint32_t)(Nc - 1));
+        bm[last >> 5] &= ~(1u << (last & 31));
+        bm[start >> 5] |= 1u << (start & 31);
+    }
+    __syncthreads();
+    const int per = (words + 1023) / 1024;
+    const int w0 = tid * per, w1 = min(words, w0 + per);
+    int cnt = 0;
+    for (int wd = w0; wd < w1; ++wd) cnt += __popc(bm[wd]);
+    part[tid] = cnt;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {  // inclusive scan
+        int v = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    int r = part[tid] - cnt;
+    for (int wd = w0; wd < w1; ++wd) {
+        uint32_t bits = bm[wd];
+        while (bits) {
+            const int i = wd * 32 + __ffs(bits) - 1;
+            bits &= bits - 1;
+            cand[r] = i;
+            cxyz[3 * (size_t)r + 0] = xyz[3 * (size_t)i + 0];
+            cxyz[3 * (size_t)r + 1] = xyz[3 * (size_t)i + 1];
+            cxyz[3 * (size_t)r + 2] = xyz[3 * (size_t)i + 2];
+            if (i == start) spos_all[b] = r;
+            ++r;
+        }
+    }
+}
+
+// One workgroup per cloud: idx[k + r] = r-th index, in the order of a second
+// permutation of [0, N), that is not among idx[0..k); r < R.
+__global__ __launch_bounds__(1024) void k_fill_perm(int N, int k, int R, uint64_t seed,
+                                                    int32_t *__restrict__ idx_all, long idx_stride,
+                                                    uint32_t *__restrict__ bitmap_all) {
+    __shared__ int part[1024];
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int words = (N + 31) / 32;
+    uint32_t *bm = bitmap_all + (size_t)b * words;
+    int32_t *idx = idx_all + b * idx_stride;
+    for (int i = tid; i < words; i += 1024) bm[i] = 0u;
+    __syncthreads();
+    for (int j = tid; j < k; j += 1024) {
+        int v = idx[j];
+        atomicOr(&bm[v >> 5], 1u << (v & 31));
+    }
+    __syncthreads();
+    const Perm p = make_perm(N, (seed + (uint64_t)b) ^ kFillSeedXor);
+    const int per = (N + 1023) / 1024;
+    const int j0 = tid * per, j1 = min(N, j0 + per);
+    int cnt = 0;
+    for (int j = j0; j < j1; ++j) {
+        const uint32_t t = perm_at(p, (uint32_t)j);
+        cnt += !((bm[t >> 5] >> (t & 31)) & 1u);
+    }
+    part[tid] = cnt;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        int v = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    int r = part[tid] - cnt;
+    for (int j = j0; j < j1 && r < R; ++j) {
+        const uint32_t t = perm_at(p, (uint32_t)j);
+        if (!((bm[t >> 5] >> (t & 31)) & 1u)) idx[k + r++] = (int32_t)t;
+    }
+}
+
 // Reference point for the multi-workgroup kernels: `iters` plain grid barriers
 // (one device-scope atomic arrive + a bounded spin on the counter per barrier).
 __global__ __launch_bounds__(256) void k_barrier_probe(unsigned *counter, int iters, int *status) {
@@ -218,6 +364,24 @@ hipError_t launch_fill(int B, int N, int k, int R, int32_t *idx, long idx_stride
                        hipStream_t s) {
     if (R <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_fill, dim3(B), dim3(1024), 0, s, N, k, R, idx, idx_stride, bitmap);
+    return hipGetLastError();
+}
+
+hipError_t launch_perm_candidates(const float *xyz, int B, int N, int Nc, int start, uint64_t seed,
+                                  uint32_t *bitmap, int32_t *cand, float *cxyz, int *spos,
+                                  hipStream_t s) {
+    const size_t words = (size_t)B * ((N + 31) / 32);
+    hipLaunchKernelGGL(k_fill_zero, dim3(blocks_for(words)), dim3(kT), 0, s, bitmap, words);
+    hipLaunchKernelGGL(k_perm_mark, dim3(blocks_for(Nc), B), dim3(kT), 0, s, N, Nc, seed, bitmap);
+    hipLaunchKernelGGL(k_perm_compact, dim3(B), dim3(1024), 0, s, xyz, N, Nc, start, seed, bitmap, cand,
+                       cxyz, spos);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_perm(int B, int N, int k, int R, uint64_t seed, int32_t *idx, long idx_stride,
+                            uint32_t *bitmap, hipStream_t s) {
+    if (R <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_perm, dim3(B), dim3(1024), 0, s, N, k, R, seed, idx, idx_stride, bitmap);
     return hipGetLastError();
 }
 

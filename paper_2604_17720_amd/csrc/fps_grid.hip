@@ -37,6 +37,7 @@ struct WaveTop {  // a worker wave's two best points and the bound on its others
 struct GridArgs {  // pointers are those of the first cloud of the launch
     const float *xyz;
     int N, M, start;
+    const int *start_dev;  // per-cloud start indices overriding `start`, or null
     int wg_per_cloud;  // the grid holds (clouds of this launch) x wg_per_cloud workgroups
     int32_t *idx_out;
     long idx_stride;   // elements between the outputs of consecutive clouds
@@ -69,6 +70,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
     a.idx_out += cloud * a.idx_stride;
     if (a.md_out) a.md_out += cloud * a.md_stride;
     a.exchange += (size_t)cloud * 2 * kBufBytes;
+    if (a.start_dev) a.start = a.start_dev[cloud];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
@@ -274,12 +276,13 @@ GridPlan plan_fps_grid(int B, int N, int num_cu) {
     return p;
 }
 
-hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start, int32_t *idx,
-                           long idx_stride, float *md, long md_stride, void *exchange, int *status,
-                           int wg_per_cloud, int max_picks, hipStream_t s) {
+hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start,
+                           const int *start_dev, int32_t *idx, long idx_stride, float *md,
+                           long md_stride, void *exchange, int *status, int wg_per_cloud,
+                           int max_picks, hipStream_t s) {
     const int G = wg_per_cloud;
     GridArgs a;
-    a.xyz = xyz; a.N = N; a.M = M; a.start = start;
+    a.xyz = xyz; a.N = N; a.M = M; a.start = start; a.start_dev = start_dev;
     a.wg_per_cloud = G;
     a.idx_out = idx; a.idx_stride = idx_stride;
     a.md_out = md; a.md_stride = md_stride;

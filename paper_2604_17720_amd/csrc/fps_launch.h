@@ -8,8 +8,10 @@ namespace ffps {
 
 // ---- fps_wg.hip: one workgroup per cloud ------------------------------------
 int wg_capacity();  // largest N the register-resident single-workgroup kernel holds
-hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, int32_t *idx,
-                         long idx_stride, float *md, long md_stride, hipStream_t s);
+// In all FPS launchers `start_dev`, when not null, is a device array with one
+// start index per cloud that overrides `start` (read by the kernel).
+hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, const int *start_dev,
+                         int32_t *idx, long idx_stride, float *md, long md_stride, hipStream_t s);
 
 // ---- fps_grid.hip: clouds spread over the whole device, resident in registers ----
 constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a launch may use
@@ -27,15 +29,16 @@ GridPlan plan_fps_grid(int B, int N, int num_cu);
 // launch.  `exchange` needs clouds * grid_exchange_bytes_per_cloud() bytes, cleared
 // (all zero) on the same stream.  status[0] receives an error code if a
 // workgroup gives up, status[1] the largest number of exchange rounds a cloud took.
-hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start, int32_t *idx,
-                           long idx_stride, float *md, long md_stride, void *exchange, int *status,
-                           int wg_per_cloud, int max_picks, hipStream_t s);
+hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start,
+                           const int *start_dev, int32_t *idx, long idx_stride, float *md,
+                           long md_stride, void *exchange, int *status, int wg_per_cloud,
+                           int max_picks, hipStream_t s);
 
 // ---- fps_stream.hip: one cloud over the whole device, streamed from HBM ------
 // `mind` is an [N] fp32 scratch array; `exchange` and `status` as for the grid kernel.
-hipError_t launch_fps_stream(const float *xyz, float *mind, int N, int M, int start, int32_t *idx,
-                             float *md, void *exchange, int *status, int num_cu, int max_picks,
-                             hipStream_t s);
+hipError_t launch_fps_stream(const float *xyz, float *mind, int N, int M, int start,
+                             const int *start_dev, int32_t *idx, float *md, void *exchange,
+                             int *status, int num_cu, int max_picks, hipStream_t s);
 
 // ---- aux.hip: small helper kernels -------------------------------------------
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
@@ -50,6 +53,15 @@ hipError_t launch_map_candidates(const int32_t *loc, long loc_stride, int B, int
 // idx[b][k + j] = j-th strided rank of the indices not in idx[b][0..k)
 hipError_t launch_fill(int B, int N, int k, int R, int32_t *idx, long idx_stride,
                        uint32_t *bitmap, hipStream_t s);
+// Seeded random candidate set of cloud b (seed + b): ascending list cand[b][0..Nc),
+// its coordinates cxyz[b][0..Nc), and spos[b] = position of `start` in the list.
+hipError_t launch_perm_candidates(const float *xyz, int B, int N, int Nc, int start, uint64_t seed,
+                                  uint32_t *bitmap, int32_t *cand, float *cxyz, int *spos,
+                                  hipStream_t s);
+// idx[b][k + r], r < R = first R indices, in the order of a second seeded permutation,
+// that are not in idx[b][0..k)
+hipError_t launch_fill_perm(int B, int N, int k, int R, uint64_t seed, int32_t *idx, long idx_stride,
+                            uint32_t *bitmap, hipStream_t s);
 // dst[b][j] = xyz[b][sel[b][j]] for j < S
 hipError_t launch_gather_points(const float *xyz, int B, int N, const int32_t *sel,
                                 long sel_stride, int S, float *dst, hipStream_t s);

@@ -24,6 +24,7 @@ struct StreamArgs {
     const float *xyz;
     float *mind;  // [N] running minimum squared distance (workspace; written before read)
     int N, M, start;
+    const int *start_dev;  // start index overriding `start`, or null
     int chunk;  // points per workgroup, a multiple of 4
     int32_t *idx_out;
     float *md_out;
@@ -34,6 +35,7 @@ struct StreamArgs {
 };
 
 __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
+    if (a.start_dev) a.start = a.start_dev[0];
     constexpr int NT = kStreamThreads, NW = NT / kWave;
     __shared__ RoundLds L;
     __shared__ Top3 wtop[NW];
@@ -199,16 +201,16 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
 
 }  // namespace
 
-hipError_t launch_fps_stream(const float *xyz, float *mind, int N, int M, int start, int32_t *idx,
-                             float *md, void *exchange, int *status, int num_cu, int max_picks,
-                             hipStream_t s) {
+hipError_t launch_fps_stream(const float *xyz, float *mind, int N, int M, int start,
+                             const int *start_dev, int32_t *idx, float *md, void *exchange,
+                             int *status, int num_cu, int max_picks, hipStream_t s) {
     int maxG = num_cu < kMaxGridWG ? num_cu : kMaxGridWG;
     // a workgroup pass covers 4096 points per step; do not spread thinner than that
     int G = (N + 4095) / 4096;
     if (G > maxG) G = maxG;
     if (G < 1) G = 1;
     StreamArgs a;
-    a.xyz = xyz; a.mind = mind; a.N = N; a.M = M; a.start = start;
+    a.xyz = xyz; a.mind = mind; a.N = N; a.M = M; a.start = start; a.start_dev = start_dev;
     a.chunk = ((N + G - 1) / G + 3) / 4 * 4;
     a.idx_out = idx; a.md_out = md;
     a.exchange = (char *)exchange; a.status = status;

@@ -21,13 +21,15 @@ struct WaveSlot {  // what one wave reports per pick
 
 template <int NT, int P>
 __global__ __launch_bounds__(NT) void k_fps_wg(const float *__restrict__ xyz_all, int N, int M,
-                                               int start, int32_t *__restrict__ idx_all,
+                                               int start_in, const int *__restrict__ start_dev,
+                                               int32_t *__restrict__ idx_all,
                                                long idx_stride, float *__restrict__ md_all,
                                                long md_stride) {
     constexpr int NW = NT / kWave;
     __shared__ WaveSlot slots[2][NW > 1 ? NW : 1];
 
     const int b = blockIdx.x;
+    const int start = start_dev ? start_dev[b] : start_in;
     const float *xyz = xyz_all + (size_t)b * N * 3;
     int32_t *idx_out = idx_all + (size_t)b * idx_stride;
     float *md_out = md_all ? md_all + (size_t)b * md_stride : nullptr;
@@ -113,9 +115,10 @@ __global__ __launch_bounds__(NT) void k_fps_wg(const float *__restrict__ xyz_all
 }
 
 template <int NT, int P>
-static hipError_t launch_wg_t(const float *xyz, int B, int N, int M, int start, int32_t *idx,
-                              long idx_stride, float *md, long md_stride, hipStream_t s) {
-    hipLaunchKernelGGL((k_fps_wg<NT, P>), dim3(B), dim3(NT), 0, s, xyz, N, M, start, idx,
+static hipError_t launch_wg_t(const float *xyz, int B, int N, int M, int start, const int *start_dev,
+                              int32_t *idx, long idx_stride, float *md, long md_stride,
+                              hipStream_t s) {
+    hipLaunchKernelGGL((k_fps_wg<NT, P>), dim3(B), dim3(NT), 0, s, xyz, N, M, start, start_dev, idx,
                        idx_stride, md, md_stride);
     return hipGetLastError();
 }
@@ -123,11 +126,11 @@ static hipError_t launch_wg_t(const float *xyz, int B, int N, int M, int start, 
 int wg_capacity() { return 1024 * 24; }
 
 // Shapes are ordered by capacity; the first one that holds N is used.
-hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, int32_t *idx,
-                         long idx_stride, float *md, long md_stride, hipStream_t s) {
+hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, const int *start_dev,
+                         int32_t *idx, long idx_stride, float *md, long md_stride, hipStream_t s) {
 #define FFPS_WG_CASE(NT, P)         \
     if (N <= (NT) * (P))            \
-        return launch_wg_t<NT, P>(xyz, B, N, M, start, idx, idx_stride, md, md_stride, s);
+        return launch_wg_t<NT, P>(xyz, B, N, M, start, start_dev, idx, idx_stride, md, md_stride, s);
     FFPS_WG_CASE(64, 4)
     FFPS_WG_CASE(256, 2)
     FFPS_WG_CASE(256, 4)

@@ -45,7 +45,7 @@ def test_prune_sizes_match_golden_table():
 
 @pytest.mark.parametrize("args", [
     (0, 1, 1, 1, 3), (10, 0, 1, 1, 3), (10, 11, 1, 1, 3), (10, 5, 0, 4, 3), (10, 5, 5, 4, 3),
-    (10, 5, 1, 0, 3), (10, 5, 1, 4, 4), (100, 50, 1, 4, 1),   # k = 50 > N' = 25
+    (10, 5, 1, 0, 3), (10, 5, 1, 4, 8), (100, 50, 1, 4, 1),   # k = 50 > N' = 25
 ])
 def test_prune_sizes_rejects(args):
     with pytest.raises(fb.FlashFPSError) as e:
@@ -89,7 +89,7 @@ def test_entry_points_validate_before_touching_the_device():
 
     k = ctypes.c_int(-7)
     def prune(kn=1, kd=4, flags=3, M=10, wsb=big):
-        return L.ffps_prune(fake, 1, 100, M, 0, kn, kd, flags, 0, fake, ctypes.byref(k), fake, wsb, null)
+        return L.ffps_prune(fake, 1, 100, M, 0, kn, kd, flags, 0, 0, fake, ctypes.byref(k), fake, wsb, null)
     assert prune(kn=0) == fb.FFPS_ERR_INVALID_ARG
     assert prune(kn=5) == fb.FFPS_ERR_INVALID_ARG
     assert prune(flags=8) == fb.FFPS_ERR_INVALID_ARG
@@ -99,7 +99,7 @@ def test_entry_points_validate_before_touching_the_device():
 
     def stages(ms, mode=0, L_=None):
         arr = (ctypes.c_int * len(ms))(*ms)
-        return L.ffps_cached_stages(fake, 1, 100, len(ms) if L_ is None else L_, arr, 0, 1, 1, 0,
+        return L.ffps_cached_stages(fake, 1, 100, len(ms) if L_ is None else L_, arr, 0, 1, 1, 0, 0,
                                     mode, 0, fake, fake, big, null)
     assert stages([50, 60]) == fb.FFPS_ERR_INVALID_ARG           # increasing
     assert stages([101]) == fb.FFPS_ERR_INVALID_ARG              # M1 > N

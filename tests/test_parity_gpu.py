@@ -158,6 +158,35 @@ def test_prune_parity(fb, oracle, kn, kd, flags, variant):
         assert np.array_equal(got.cpu().numpy()[0], ref)
 
 
+@pytest.mark.parametrize("kn,kd", [(1, 4), (2, 3), (1, 1)])
+@pytest.mark.parametrize("flags", [1 | 4, 2 | 4, 3 | 4])
+def test_random_prune_parity(fb, oracle, kn, kd, flags):
+    """Seeded random sub-sample and fill (FFPS_FLAG_PERM): same permutation on both
+    sides, so indices must agree bit for bit."""
+    x = inputs.make_config(4, N=20011)
+    for start, seed, variant in ((0, 0, 0), (13579, 2 ** 40 + 17, GRID), (20010, 2 ** 64 - 1, 0)):
+        print(f"perm prune keep={kn}/{kd} flags={flags} start={start} seed={seed}", flush=True)
+        ws = fb.make_workspace(1, 20011, 3000)
+        got, k = fb.ffps_prune(_dev(x), 3000, kn, kd, flags, start, variant, workspace=ws, seed=seed)
+        assert fb.ffps_last_status(ws) == 0
+        ref = oracle.fps_prune(x[0], 3000, kn, kd, flags, start, seed)
+        assert np.array_equal(got.cpu().numpy()[0], ref)
+
+
+def test_random_prune_batched_and_stages(fb, oracle):
+    x = inputs.make_config(3, B=5, N=6000)
+    got, k = fb.ffps_prune(_dev(x), 1500, 1, 2, 7, 3, seed=1000)      # cloud b uses seed + b
+    assert np.array_equal(got.cpu().numpy(), oracle.fps_prune(x, 1500, 1, 2, 7, 3, 1000))
+    ms = (1500, 375, 90)
+    for mode in (0, 1):
+        outs = fb.ffps_cached_stages(_dev(x), ms, mode, 1, 4, 7, 0, seed=77)
+        flat = np.concatenate([o.cpu().numpy() for o in outs], axis=1)
+        assert np.array_equal(flat, oracle.fps_stages(x, ms, mode, 1, 4, 7, 0, 77))
+    small = inputs.make_config(2, B=4)
+    got, _ = fb.ffps_prune(_dev(small), 512, 1, 4, 7, 0, seed=5)
+    assert np.array_equal(got.cpu().numpy(), oracle.fps_prune(small, 512, 1, 4, 7, 0, 5))
+
+
 def test_prune_batched_small_clouds(fb, oracle):
     x = inputs.make_config(2, B=5)
     got, k = fb.ffps_prune(_dev(x), 512, 1, 2, 3, 0)
