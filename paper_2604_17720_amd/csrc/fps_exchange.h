@@ -437,9 +437,11 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
         }
     }
     // workgroup 0 records the picks (the same wave wrote pk_idx / pk_val)
-    if (w == 0 && lane < cnt) {
-        idx_out[npicked + lane] = (int32_t)L.pk_idx[lane];
-        if (md_out) md_out[npicked + lane] = u2f(L.pk_val[lane]);
+    if (w == 0) {
+        for (int c = lane; c < cnt; c += kWave) {
+            idx_out[npicked + c] = (int32_t)L.pk_idx[c];
+            if (md_out) md_out[npicked + c] = u2f(L.pk_val[c]);
+        }
     }
     return cnt;
 }

@@ -88,8 +88,10 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         s.x = f2u(a.xyz[3 * (size_t)a.start + 0]);
         s.y = f2u(a.xyz[3 * (size_t)a.start + 1]);
         s.z = f2u(a.xyz[3 * (size_t)a.start + 2]);
-        s.w = lane == 0 ? 0u : 0xffffffffu;
-        lds_write16(pk_off + lane * 16, s);
+        for (int c = lane; c < kMaxPicksPerRound; c += kWave) {
+            s.w = c == 0 ? 0u : 0xffffffffu;
+            lds_write16(pk_off + c * 16, s);
+        }
         if (lane == 0) {
             vfin[1] = 1;
             vfin[0] = 0;
@@ -259,7 +261,11 @@ long grid_capacity(int num_cu) {
 }
 
 GridPlan plan_fps_grid(int B, int N, int num_cu) {
+#ifdef FFPS_EXP_MAXG
+    const int maxG = FFPS_EXP_MAXG;
+#else
     const int maxG = num_cu < kMaxGridWG ? num_cu : kMaxGridWG;
+#endif
     // at least 128 points per workgroup before another CU is worth a record ...
     int want = (N + 127) / 128;
     if (want > maxG) want = maxG;
@@ -292,14 +298,13 @@ hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start
     const int num_wg = clouds * G;
 #define FFPS_GRID_CASE(NWK, P) \
     if (per_wg <= (NWK) * kWave * (P)) return launch_t<NWK, P>(a, num_wg, s);
+    // one worker wave per SIMD for small slices, two from 385 points per workgroup on
     FFPS_GRID_CASE(3, 1)
     FFPS_GRID_CASE(3, 2)
-    FFPS_GRID_CASE(3, 3)
-    FFPS_GRID_CASE(3, 4)
-    FFPS_GRID_CASE(3, 5)
-    FFPS_GRID_CASE(3, 6)
-    FFPS_GRID_CASE(3, 7)
-    FFPS_GRID_CASE(3, 8)
+    FFPS_GRID_CASE(6, 2)
+    FFPS_GRID_CASE(6, 3)
+    FFPS_GRID_CASE(6, 4)
+    FFPS_GRID_CASE(6, 5)
     FFPS_GRID_CASE(6, 6)
     FFPS_GRID_CASE(6, 8)
     FFPS_GRID_CASE(12, 6)

@@ -15,7 +15,10 @@ hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, const
 
 // ---- fps_grid.hip: clouds spread over the whole device, resident in registers ----
 constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a launch may use
-constexpr int kMaxPicksPerRound = 64;
+#ifndef FFPS_MAX_PICKS
+#define FFPS_MAX_PICKS 128
+#endif
+constexpr int kMaxPicksPerRound = FFPS_MAX_PICKS;  // picks one exchange round may deliver
 size_t grid_exchange_bytes_per_cloud();  // bytes of one cloud's exchange area (two record buffers)
 long grid_capacity(int num_cu);          // largest N the register-resident grid kernel holds
 // How B clouds of N points are laid over the device: workgroups per cloud, and
