@@ -106,3 +106,20 @@ def test_entry_points_validate_before_touching_the_device():
     assert stages([50, 0]) == fb.FFPS_ERR_INVALID_ARG
     assert stages([50], mode=2) == fb.FFPS_ERR_INVALID_ARG
     assert stages([50], L_=0) == fb.FFPS_ERR_INVALID_ARG
+
+
+def test_torch_operators_register_and_infer_shapes():
+    """torch.ops.flashfps.* exist and their shape functions work on fake tensors
+    (no kernel runs, so no GPU is needed)."""
+    import torch
+    from torch._subclasses.fake_tensor import FakeTensorMode
+
+    import paper_2604_17720_amd.torch_ops  # noqa: F401
+    with FakeTensorMode():
+        x = torch.empty(2, 100, 3, device="cuda")
+        assert torch.ops.flashfps.fps_exact(x, 10, 0).shape == (2, 10)
+        assert torch.ops.flashfps.fps_prune(x, 12, 1, 4, 3, 0, 0).shape == (2, 12)
+        st = torch.ops.flashfps.fps_stages(x, [10, 5], 0, 1, 1, 0, 0, 0)
+        assert st.shape == (2, 15) and st.dtype == torch.int32
+        idx = torch.empty(2, 7, dtype=torch.int32, device="cuda")
+        assert torch.ops.flashfps.gather_rows(x, idx).shape == (2, 7, 3)

@@ -253,6 +253,22 @@ def test_gather_rows_of_stage_outputs(fb):
         fb.ffps_gather_rows(_dev(x), outs[0].to(torch.int64))
 
 
+def test_torch_operators(fb, oracle):
+    import torch
+
+    import paper_2604_17720_amd.torch_ops  # noqa: F401
+    x = inputs.make_config(2, B=3)
+    xd = _dev(x)
+    idx = torch.ops.flashfps.fps_exact(xd, 200, 0)
+    assert np.array_equal(idx.cpu().numpy(), oracle.fps_exact(x, 200, 0))
+    pr = torch.ops.flashfps.fps_prune(xd, 200, 1, 2, 3, 0, 0)
+    assert np.array_equal(pr.cpu().numpy(), oracle.fps_prune(x, 200, 1, 2, 3, 0))
+    st = torch.ops.flashfps.fps_stages(xd, [200, 50], 1, 1, 1, 0, 0, 0)
+    assert np.array_equal(st.cpu().numpy(), oracle.fps_stages(x, (200, 50), 1))
+    pts = torch.ops.flashfps.gather_rows(xd, idx)
+    assert np.array_equal(pts.cpu().numpy()[1], x[1][idx.cpu().numpy()[1]])
+
+
 # ------------------------------------------------- full benchmark sizes ----
 def _radius64(x, sel):
     """Coverage radius via a k-d tree in float64 (only ratios of it are used)."""
