@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes one launch of the dominant kernel really moves, from the hardware
 # counters in profiles/k_fps_grid_config4_hbm_counters.md (FETCH_SIZE x 2.000 +
 # WRITE_SIZE x 1.000, calibrated on a 256 MiB copy): exchange records only.
-MEASURED_TRAFFIC_BYTES = 2.000 * 226589.75 * 1024 + 1.000 * 25459.10 * 1024
+MEASURED_TRAFFIC_BYTES = 2.000 * 210921.38 * 1024 + 1.000 * 25731.39 * 1024
 
 
 def updates_of_chain(sizes):
@@ -142,22 +142,26 @@ def main():
         "updates_per_step": upd_step,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": "k_fps_grid<3,5> (exact FPS, N=200000, M=50000)",
+                     "kernel": "k_fps_grid<6,3> (exact FPS, N=200000, M=50000)",
                      "algorithmic_bytes_per_launch": upd_exact * BYTES_PER_UPDATE,
                      "note": "points and min-distances stay in registers, so achieved is the "
                              "HBM-equivalent rate of a streaming loop, not bytes moved"},
     }
 
-    # One plain grid barrier in the same launch shape, and one exchange round that
-    # delivers a single pick: the per-pick latency of the multi-pick kernel is
-    # quoted against both.
+    # One plain grid barrier in the same launch shape (256 workgroups), and one
+    # exchange round that delivers a single pick: the per-pick latency of the
+    # multi-pick kernel is quoted against both.  The one-pick run uses the first
+    # 100,000 points so that it is a different kernel instantiation and does not
+    # mix into the profiler's average for the dominant kernel; the cost of a round
+    # does not depend on the number of points per workgroup.
     result["grid_barrier_us"] = fb.ffps_barrier_probe(20000, workspace=ws)
-    m_one = 4001
+    n_one, m_one = 100000, 4001
+    x_one = x[:, :n_one].contiguous()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     one = fb.variant_with_picks(fb.FFPS_VARIANT_GRID, 1)
-    fb.ffps_exact(x, m_one, 0, one, workspace=ws)
+    fb.ffps_exact(x_one, m_one, 0, one, workspace=ws)
     e0.record()
-    fb.ffps_exact(x, m_one, 0, one, workspace=ws)
+    fb.ffps_exact(x_one, m_one, 0, one, workspace=ws)
     e1.record()
     torch.cuda.synchronize()
     result["us_per_round_one_pick"] = e0.elapsed_time(e1) * 1e3 / (m_one - 1)
