@@ -95,7 +95,7 @@ int resolve_variant(int B, int N, int variant, const Device &dev) {
         // one workgroup per cloud.  Otherwise clusters of workgroups per cloud.
         const bool fits_wg = N <= wg_capacity();
         const bool fits_grid = N <= grid_capacity(dev.num_cu);
-        if (fits_wg && (N <= 2048 || !fits_grid || plan_fps_grid(B, N, dev.num_cu).wg_per_cloud < 16))
+        if (fits_wg && (N <= wgm_capacity() || !fits_grid || plan_fps_grid(B, N, dev.num_cu).wg_per_cloud < 16))
             v = FFPS_VARIANT_WG;
         else if (N <= grid_capacity(dev.num_cu))
             v = FFPS_VARIANT_GRID;
@@ -115,7 +115,8 @@ int run_exact(const float *xyz, int B, int N, int M, int start, const int *start
     int v = resolve_variant(B, N, variant, dev);
     if (v < 0) return v;
     if (v == FFPS_VARIANT_WG)
-        return hip_rc(launch_fps_wg(xyz, B, N, M, start, start_dev, idx, idx_stride, md, md_stride, s));
+        return hip_rc(launch_fps_wg(xyz, B, N, M, start, start_dev, idx, idx_stride, md, md_stride,
+                                    variant_picks(variant), (int *)(ws + w.status), s));
     if (v == FFPS_VARIANT_GRID) {
         const GridPlan plan = plan_fps_grid(B, N, dev.num_cu);
         for (int b = 0; b < B; b += plan.clouds_per_launch) {

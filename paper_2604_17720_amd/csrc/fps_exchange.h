@@ -104,6 +104,25 @@ __device__ __forceinline__ u32x4 lds_read16(uint32_t off) {
     return r;
 }
 
+// The same read in two halves, so that work can overlap its latency: r is not
+// valid before lds_wait16(r) has run.
+__device__ __forceinline__ void lds_issue16(u32x4 &r, uint32_t off) {
+    asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(off) : "memory");
+}
+__device__ __forceinline__ void lds_wait16(u32x4 &r) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r) : : "memory");
+}
+// 8-byte LDS word written and read by one instruction each.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void lds_write8(uint32_t off, u32x2 v) {
+    asm volatile("ds_write_b64 %0, %1" : : "v"(off), "v"(v) : "memory");
+}
+__device__ __forceinline__ u32x2 lds_read8(uint32_t off) {
+    u32x2 r;
+    asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(off) : "memory");
+    return r;
+}
+
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return ~wave_max_u32(~v); }
 // Reductions over lanes 0..15 only (other lanes must pass the identity), wave-uniform.
 __device__ __forceinline__ uint32_t row_max_uniform(uint32_t v) {
@@ -166,15 +185,15 @@ struct RoundLds {
     __attribute__((aligned(16))) u32x4 pk[kMaxPicksPerRound];  // picks of the round: {x, y, z, seq}
     uint32_t pk_idx[kMaxPicksPerRound];  // index of each pick of the round
     uint32_t pk_val[kMaxPicksPerRound];  // and the value it was picked with
-    uint32_t cmp_v[2 * kWave];           // compacted live candidates
-    uint32_t cmp_i[2 * kWave];
-    float cmp_x[2 * kWave], cmp_y[2 * kWave], cmp_z[2 * kWave];
+    __attribute__((aligned(16))) u32x4 cmp_a[2 * kWave];  // compacted live candidates: {value, index, x, y}
+    float cmp_z[2 * kWave];                               // and z
 };
 
 // Counters of a profiling build (workgroup 0 only).
 struct RoundProf {
     uint32_t acc[8];   // 100 MHz ticks per phase; [5], [6]: rounds on the packed paths; [7]: polls
     uint32_t loop[4];  // shader cycles and picks inside the two packed loops
+    uint32_t sub[4];   // shader cycles of the replay set-up: bounds, counting, compaction
     uint64_t last;
 };
 #ifdef FFPS_PROFILE
@@ -192,6 +211,241 @@ struct RoundProf {
     } while (0)
 #endif
 
+// Replay of the greedy rule of Eq. 1 on KC candidates per lane of ONE full wave
+// (value bits cv, point index ci, coordinates cx/cy/cz; a candidate that does
+// not exist has value 0 and index kNoIndex), given lb = the lane's share of the
+// bounds on all points that are not candidates.  Pick number c of the round is
+// written as {x, y, z, npicked + c} to L.pk[c] (16-byte LDS writes, in pick
+// order, so other waves may consume them while the replay is still running),
+// its index and value to L.pk_idx[c] / L.pk_val[c].  Returns the number of
+// picks (1 .. cap).  The candidate arrays are used up.
+template <int KC>
+__device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv)[KC],
+                                            uint32_t (&ci)[KC], float (&cx)[KC], float (&cy)[KC],
+                                            float (&cz)[KC], uint32_t lb, int npicked, int cap,
+                                            RoundProf *prof) {
+    const uint32_t pk_off = lds_offset(L.pk);
+#ifdef FFPS_PROFILE
+    uint64_t sc = clock64();
+#define FFPS_SUB(i)                              \
+    do {                                         \
+        if (prof) {                              \
+            uint64_t n_ = clock64();             \
+            prof->sub[i] += (uint32_t)(n_ - sc); \
+            sc = n_;                             \
+        }                                        \
+    } while (0)
+#else
+#define FFPS_SUB(i) \
+    do {            \
+    } while (0)
+#endif
+    const uint32_t Bound = wave_max_u32(lb);
+    // Hand pick number c of this round to the other waves (one 16-byte LDS write)
+    // and note its index and value; `mine` holds in exactly one lane.
+    auto emit = [&](bool mine, int c, uint32_t idx, uint32_t vbits, float ex, float ey, float ez) {
+        if (mine) {
+            u32x4 s;
+            s.x = f2u(ex); s.y = f2u(ey); s.z = f2u(ez); s.w = (uint32_t)(npicked + c);
+            lds_write16(pk_off + c * 16, s);
+            L.pk_idx[c] = idx;
+            L.pk_val[c] = vbits;
+        }
+    };
+    auto lane_best = [&](uint32_t &bv, uint32_t &bi, int &bq) {
+        bv = cv[0]; bi = ci[0]; bq = 0;
+#pragma unroll
+        for (int q = 1; q < KC; ++q) {
+            const bool better = cv[q] > bv || (cv[q] == bv && ci[q] < bi);
+            bv = better ? cv[q] : bv;
+            bi = better ? ci[q] : bi;
+            bq = better ? q : bq;
+        }
+    };
+    auto wmin = [](uint32_t v) { return wave_min_u32(v); };
+    uint32_t lv = cv[0];
+#pragma unroll
+    for (int q = 1; q < KC; ++q) lv = umax(lv, cv[q]);
+    uint32_t V = wave_max_u32(lv);  // best candidate value
+    int cnt = 0;
+    int pl;
+    float px, py, pz;
+    // Only candidates above the bound can be picked after the first pick, and
+    // when the best candidate is above it the first pick is one of them too:
+    // compact them (in any order).  Any threshold T >= Bound serves as well (the
+    // round then ends when the best candidate is no longer above T), so when more
+    // than 128 candidates are above the bound T is raised to the largest
+    // third-best candidate value of any lane, which leaves at most two per lane.
+    uint32_t T = Bound;
+    int total = 0, before = 0;
+    FFPS_SUB(0);
+    if (V > Bound && cap > 1) {
+        // total = live candidates of the wave, before = those of lower lanes: the
+        // per-lane count goes through one ballot per bit of it
+        auto count_live = [&]() {
+            uint32_t c = 0u;
+#pragma unroll
+            for (int q = 0; q < KC; ++q) c += cv[q] > T ? 1u : 0u;
+            total = 0;
+            before = 0;
+#pragma unroll
+            for (int bit = 0; (1 << bit) <= KC; ++bit) {
+                const uint64_t mk = __builtin_amdgcn_ballot_w64((c >> bit) & 1u);
+                total += __builtin_popcountll(mk) << bit;
+                before += (int)__builtin_amdgcn_mbcnt_hi(
+                              (uint32_t)(mk >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mk, 0u))
+                          << bit;
+            }
+        };
+        count_live();
+        if (total > 2 * kWave) {
+            uint32_t t1 = 0u, t2 = 0u, t3 = 0u;
+#pragma unroll
+            for (int q = 0; q < KC; ++q) {
+                const uint32_t v = cv[q];
+                t3 = umax(t3, v < t2 ? v : t2);
+                t2 = umax(t2, v < t1 ? v : t1);
+                t1 = umax(t1, v);
+            }
+            T = umax(Bound, wave_max_u32(t3));
+            count_live();
+        }
+    }
+    // With at most 128 live candidates whose values lie within 2^24 ulps above
+    // the threshold, value and position fit one 32-bit key
+    //   key = (value_bits - threshold_bits) << 7 | position,
+    // and a single wave-wide max yields the best value and a lane that holds it.
+    // Values at or below the threshold saturate to 0 and end the round.  Whether other
+    // candidates hold the same value costs one ballot; only then is the index
+    // compared.
+    const bool packed = total >= 1 && total <= 2 * kWave && V - T < (1u << 24);
+    FFPS_SUB(1);
+#ifdef FFPS_PROFILE
+    if (prof && packed) prof->acc[total <= kWave ? 5 : 6] += 1;
+#endif
+    if (packed) {
+        int pos = before;
+#pragma unroll
+        for (int q = 0; q < KC; ++q) {
+            if (cv[q] > T) {
+                u32x4 r;
+                r.x = cv[q]; r.y = ci[q]; r.z = f2u(cx[q]); r.w = f2u(cy[q]);
+                L.cmp_a[pos] = r;
+                L.cmp_z[pos] = cz[q];
+                ++pos;
+            }
+        }
+        // the same wave wrote and now reads: LDS keeps its accesses in order
+        FFPS_SUB(2);
+        if (total <= kWave) {
+            // one candidate per lane: lane L takes position L
+            const bool h = lane < total;
+            const u32x4 r0 = L.cmp_a[lane];
+            uint32_t v0 = h ? r0.x : 0u;
+            const uint32_t i0 = h ? r0.y : kNoIndex;
+            const float x0 = h ? u2f(r0.z) : 0.f, y0 = h ? u2f(r0.w) : 0.f,
+                        z0 = h ? L.cmp_z[lane] : 0.f;
+#ifdef FFPS_PROFILE
+            const uint64_t lc0 = clock64();
+#endif
+            while (true) {
+                const uint32_t key = (__builtin_elementwise_sub_sat(v0, T) << 7) | (uint32_t)lane;
+                const uint32_t K = wave_max_u32(key);
+                if ((K >> 7) == 0) break;  // cannot happen for the first pick
+                const uint64_t tied = __builtin_amdgcn_ballot_w64((key >> 7) == (K >> 7));
+                pl = (int)(K & 127u);
+                if (__builtin_popcountll(tied) > 1) {  // several candidates share the best value
+                    const uint32_t imin = wave_min_u32((key >> 7) == (K >> 7) ? i0 : 0xffffffffu);
+                    pl = first_lane((key >> 7) == (K >> 7) && i0 == imin);
+                }
+                px = readlane_f(x0, pl);
+                py = readlane_f(y0, pl);
+                pz = readlane_f(z0, pl);
+                emit(lane == pl, cnt, i0, v0, x0, y0, z0);  // the winning lane hands over its own
+                if (++cnt >= cap) break;
+                v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
+            }
+#ifdef FFPS_PROFILE
+            if (prof) {
+                prof->loop[0] += (uint32_t)(clock64() - lc0);
+                prof->loop[1] += cnt;
+            }
+#endif
+        } else {
+            // two candidates per lane (positions L and L + 64), the lower index first,
+            // so that a lane whose two values tie puts forward the right one
+            const int p1 = lane + kWave;
+            const bool h1 = p1 < total;  // position L itself is always taken here
+            const u32x4 r0 = L.cmp_a[lane], r1 = L.cmp_a[p1];
+            uint32_t v0 = r0.x, v1 = h1 ? r1.x : 0u;
+            uint32_t i0 = r0.y, i1 = h1 ? r1.y : kNoIndex;
+            float x0 = u2f(r0.z), y0 = u2f(r0.w), z0 = L.cmp_z[lane];
+            float x1 = h1 ? u2f(r1.z) : 0.f, y1 = h1 ? u2f(r1.w) : 0.f, z1 = h1 ? L.cmp_z[p1] : 0.f;
+            if (i1 < i0) {
+                uint32_t tu;
+                float tf;
+                tu = v0; v0 = v1; v1 = tu;
+                tu = i0; i0 = i1; i1 = tu;
+                tf = x0; x0 = x1; x1 = tf;
+                tf = y0; y0 = y1; y1 = tf;
+                tf = z0; z0 = z1; z1 = tf;
+            }
+#ifdef FFPS_PROFILE
+            const uint64_t lc0 = clock64();
+#endif
+            while (true) {
+                const uint32_t d0 = __builtin_elementwise_sub_sat(v0, T);
+                const uint32_t d1 = __builtin_elementwise_sub_sat(v1, T);
+                const bool sec = d1 > d0;  // strict: equal values put the lower index forward
+                const float bx = sec ? x1 : x0, by = sec ? y1 : y0, bz = sec ? z1 : z0;
+                const uint32_t bidx = sec ? i1 : i0;
+                const uint32_t key = ((sec ? d1 : d0) << 7) | (uint32_t)lane;
+                const uint32_t K = wave_max_u32(key);
+                if ((K >> 7) == 0) break;
+                const uint64_t tied = __builtin_amdgcn_ballot_w64((key >> 7) == (K >> 7));
+                pl = (int)(K & 127u);
+                if (__builtin_popcountll(tied) > 1) {
+                    const uint32_t imin = wave_min_u32((key >> 7) == (K >> 7) ? bidx : 0xffffffffu);
+                    pl = first_lane((key >> 7) == (K >> 7) && bidx == imin);
+                }
+                px = readlane_f(bx, pl);
+                py = readlane_f(by, pl);
+                pz = readlane_f(bz, pl);
+                emit(lane == pl, cnt, bidx, sec ? v1 : v0, bx, by, bz);
+                if (++cnt >= cap) break;
+                v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
+                v1 = f2u(fminf(u2f(v1), sqdist(x1, y1, z1, px, py, pz)));
+            }
+#ifdef FFPS_PROFILE
+            if (prof) {
+                prof->loop[2] += (uint32_t)(clock64() - lc0);
+                prof->loop[3] += cnt;
+            }
+#endif
+        }
+    } else {
+        // a single pick (best candidate not above the bound, or cap 1), or values
+        // spread too far above the threshold for the packed key: work on all
+        // candidates of every lane
+        while (true) {
+            uint32_t bv, bi;
+            int bq;
+            lane_best(bv, bi, bq);
+            V = wave_max_u32(bv);
+            if (cnt > 0 && !(V > Bound)) break;
+            pl = best_lane(bv, bi, V, wmin);
+            const int pq = readlane_i(bq, pl);
+            pick_xyz<KC>(cx, cy, cz, pq, pl, px, py, pz);
+            emit(lane == pl, cnt, bi, V, px, py, pz);
+            if (++cnt >= cap) break;
+#pragma unroll
+            for (int q = 0; q < KC; ++q)
+                cv[q] = f2u(fminf(u2f(cv[q]), sqdist(cx[q], cy[q], cz[q], px, py, pz)));
+        }
+    }
+    return cnt;
+}
+
 // One round, run by ONE full wave of workgroup w.  Publishes `in`, gathers all
 // G records, replays, writes each pick as {x, y, z, npicked + c} to L.pk[c]
 // (16-byte LDS writes, in pick order, so other waves may consume them while
@@ -202,7 +456,6 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
                                               uint32_t round, const RoundInput &in, int npicked,
                                               int cap, int32_t *idx_out, float *md_out, int *status,
                                               RoundProf *prof) {
-    const uint32_t pk_off = lds_offset(L.pk);
     // ---- publish ----
     char *buf = exchange + (size_t)(round & 1) * kBufBytes;
     if (lane == 0) {
@@ -263,179 +516,7 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
         cx[2 * q] = u2f(rb[q].x); cy[2 * q] = u2f(rb[q].y); cz[2 * q] = u2f(rb[q].z);
         cx[2 * q + 1] = u2f(rc[q].x); cy[2 * q + 1] = u2f(rc[q].y); cz[2 * q + 1] = u2f(rc[q].z);
     }
-    // ---- replay the greedy rule on the published candidates ----
-    const uint32_t Bound = wave_max_u32(lb);
-    // Hand pick number c of this round to the other waves (one 16-byte LDS write)
-    // and note its index and value; `mine` holds in exactly one lane.
-    auto emit = [&](bool mine, int c, uint32_t idx, uint32_t vbits, float ex, float ey, float ez) {
-        if (mine) {
-            u32x4 s;
-            s.x = f2u(ex); s.y = f2u(ey); s.z = f2u(ez); s.w = (uint32_t)(npicked + c);
-            lds_write16(pk_off + c * 16, s);
-            L.pk_idx[c] = idx;
-            L.pk_val[c] = vbits;
-        }
-    };
-    auto lane_best = [&](uint32_t &bv, uint32_t &bi, int &bq) {
-        bv = cv[0]; bi = ci[0]; bq = 0;
-#pragma unroll
-        for (int q = 1; q < kCPL; ++q) {
-            const bool better = cv[q] > bv || (cv[q] == bv && ci[q] < bi);
-            bv = better ? cv[q] : bv;
-            bi = better ? ci[q] : bi;
-            bq = better ? q : bq;
-        }
-    };
-    auto wmin = [](uint32_t v) { return wave_min_u32(v); };
-    uint32_t bv, bi;
-    int bq;
-    lane_best(bv, bi, bq);
-    uint32_t V = wave_max_u32(bv);
-    int cnt = 0;
-    int pl;
-    float px, py, pz;
-    // Only candidates above the bound can be picked after the first pick, and
-    // when the best candidate is above it the first pick is one of them too:
-    // compact them (in any order).
-    int total = 0, before = 0;
-    if (V > Bound && cap > 1) {
-        const uint64_t lt = ((uint64_t)1 << lane) - 1;
-#pragma unroll
-        for (int q = 0; q < kCPL; ++q) {
-            uint64_t mk = __builtin_amdgcn_ballot_w64(cv[q] > Bound);
-            total += __builtin_popcountll(mk);
-            before += __builtin_popcountll(mk & lt);
-        }
-    }
-    // With at most 128 live candidates whose values lie within 2^24 ulps above
-    // the bound, value and position fit one 32-bit key
-    //   key = (value_bits - bound_bits) << 7 | position,
-    // and a single wave-wide max yields the best value and a lane that holds it.
-    // Values at or below the bound saturate to 0 and end the round.  Whether other
-    // candidates hold the same value costs one ballot; only then is the index
-    // compared.
-    const bool packed = total >= 1 && total <= 2 * kWave && V - Bound < (1u << 24);
-#ifdef FFPS_PROFILE
-    if (prof && packed) prof->acc[total <= kWave ? 5 : 6] += 1;
-#endif
-    if (packed) {
-        int pos = before;
-#pragma unroll
-        for (int q = 0; q < kCPL; ++q) {
-            if (cv[q] > Bound) {
-                L.cmp_v[pos] = cv[q];
-                L.cmp_i[pos] = ci[q];
-                L.cmp_x[pos] = cx[q];
-                L.cmp_y[pos] = cy[q];
-                L.cmp_z[pos] = cz[q];
-                ++pos;
-            }
-        }
-        // the same wave wrote and now reads: LDS keeps its accesses in order
-        if (total <= kWave) {
-            // one candidate per lane: lane L takes position L
-            const bool h = lane < total;
-            uint32_t v0 = h ? L.cmp_v[lane] : 0u;
-            const uint32_t i0 = h ? L.cmp_i[lane] : kNoIndex;
-            const float x0 = h ? L.cmp_x[lane] : 0.f, y0 = h ? L.cmp_y[lane] : 0.f,
-                        z0 = h ? L.cmp_z[lane] : 0.f;
-#ifdef FFPS_PROFILE
-            const uint64_t lc0 = clock64();
-#endif
-            while (true) {
-                const uint32_t key = (__builtin_elementwise_sub_sat(v0, Bound) << 7) | (uint32_t)lane;
-                const uint32_t K = wave_max_u32(key);
-                if ((K >> 7) == 0) break;  // cannot happen for the first pick
-                const uint64_t tied = __builtin_amdgcn_ballot_w64((key >> 7) == (K >> 7));
-                pl = (int)(K & 127u);
-                if (__builtin_popcountll(tied) > 1) {  // several candidates share the best value
-                    const uint32_t imin = wave_min_u32((key >> 7) == (K >> 7) ? i0 : 0xffffffffu);
-                    pl = first_lane((key >> 7) == (K >> 7) && i0 == imin);
-                }
-                px = readlane_f(x0, pl);
-                py = readlane_f(y0, pl);
-                pz = readlane_f(z0, pl);
-                emit(lane == pl, cnt, i0, v0, x0, y0, z0);  // the winning lane hands over its own
-                if (++cnt >= cap) break;
-                v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
-            }
-#ifdef FFPS_PROFILE
-            if (prof) {
-                prof->loop[0] += (uint32_t)(clock64() - lc0);
-                prof->loop[1] += cnt;
-            }
-#endif
-        } else {
-            // two candidates per lane (positions 2L and 2L+1), the lower index first,
-            // so that a lane whose two values tie puts forward the right one
-            const int p0 = 2 * lane, p1 = 2 * lane + 1;
-            const bool h0 = p0 < total, h1 = p1 < total;
-            uint32_t v0 = h0 ? L.cmp_v[p0] : 0u, v1 = h1 ? L.cmp_v[p1] : 0u;
-            uint32_t i0 = h0 ? L.cmp_i[p0] : kNoIndex, i1 = h1 ? L.cmp_i[p1] : kNoIndex;
-            float x0 = h0 ? L.cmp_x[p0] : 0.f, y0 = h0 ? L.cmp_y[p0] : 0.f, z0 = h0 ? L.cmp_z[p0] : 0.f;
-            float x1 = h1 ? L.cmp_x[p1] : 0.f, y1 = h1 ? L.cmp_y[p1] : 0.f, z1 = h1 ? L.cmp_z[p1] : 0.f;
-            if (i1 < i0) {
-                uint32_t tu;
-                float tf;
-                tu = v0; v0 = v1; v1 = tu;
-                tu = i0; i0 = i1; i1 = tu;
-                tf = x0; x0 = x1; x1 = tf;
-                tf = y0; y0 = y1; y1 = tf;
-                tf = z0; z0 = z1; z1 = tf;
-            }
-#ifdef FFPS_PROFILE
-            const uint64_t lc0 = clock64();
-#endif
-            while (true) {
-                const uint32_t d0 = __builtin_elementwise_sub_sat(v0, Bound);
-                const uint32_t d1 = __builtin_elementwise_sub_sat(v1, Bound);
-                const bool sec = d1 > d0;  // strict: equal values put the lower index forward
-                const float bx = sec ? x1 : x0, by = sec ? y1 : y0, bz = sec ? z1 : z0;
-                const uint32_t bidx = sec ? i1 : i0;
-                const uint32_t key = ((sec ? d1 : d0) << 7) | (uint32_t)lane;
-                const uint32_t K = wave_max_u32(key);
-                if ((K >> 7) == 0) break;
-                const uint64_t tied = __builtin_amdgcn_ballot_w64((key >> 7) == (K >> 7));
-                pl = (int)(K & 127u);
-                if (__builtin_popcountll(tied) > 1) {
-                    const uint32_t imin = wave_min_u32((key >> 7) == (K >> 7) ? bidx : 0xffffffffu);
-                    pl = first_lane((key >> 7) == (K >> 7) && bidx == imin);
-                }
-                px = readlane_f(bx, pl);
-                py = readlane_f(by, pl);
-                pz = readlane_f(bz, pl);
-                emit(lane == pl, cnt, bidx, sec ? v1 : v0, bx, by, bz);
-                if (++cnt >= cap) break;
-                v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
-                v1 = f2u(fminf(u2f(v1), sqdist(x1, y1, z1, px, py, pz)));
-            }
-#ifdef FFPS_PROFILE
-            if (prof) {
-                prof->loop[2] += (uint32_t)(clock64() - lc0);
-                prof->loop[3] += cnt;
-            }
-#endif
-        }
-    } else {
-        // a single pick (best candidate not above the bound, or cap 1), more than
-        // 128 live candidates, or values spread too far above the bound for the
-        // packed key: work on all eight candidates per lane
-        while (true) {
-            if (cnt > 0) {
-                lane_best(bv, bi, bq);
-                V = wave_max_u32(bv);
-                if (!(V > Bound)) break;
-            }
-            pl = best_lane(bv, bi, V, wmin);
-            const int pq = readlane_i(bq, pl);
-            pick_xyz<kCPL>(cx, cy, cz, pq, pl, px, py, pz);
-            emit(lane == pl, cnt, bi, V, px, py, pz);
-            if (++cnt >= cap) break;
-#pragma unroll
-            for (int q = 0; q < kCPL; ++q)
-                cv[q] = f2u(fminf(u2f(cv[q]), sqdist(cx[q], cy[q], cz[q], px, py, pz)));
-        }
-    }
+    const int cnt = replay_round<kCPL>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
     // workgroup 0 records the picks (the same wave wrote pk_idx / pk_val)
     if (w == 0) {
         for (int c = lane; c < cnt; c += kWave) {

@@ -6,19 +6,25 @@
 
 namespace ffps {
 
-// ---- fps_wg.hip: one workgroup per cloud ------------------------------------
-int wg_capacity();  // largest N the register-resident single-workgroup kernel holds
-// In all FPS launchers `start_dev`, when not null, is a device array with one
-// start index per cloud that overrides `start` (read by the kernel).
-hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, const int *start_dev,
-                         int32_t *idx, long idx_stride, float *md, long md_stride, hipStream_t s);
-
-// ---- fps_grid.hip: clouds spread over the whole device, resident in registers ----
-constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a launch may use
 #ifndef FFPS_MAX_PICKS
 #define FFPS_MAX_PICKS 128
 #endif
-constexpr int kMaxPicksPerRound = FFPS_MAX_PICKS;  // picks one exchange round may deliver
+constexpr int kMaxPicksPerRound = FFPS_MAX_PICKS;  // picks one round may deliver
+
+// ---- fps_wg.hip: one workgroup per cloud ------------------------------------
+int wg_capacity();   // largest N the single-workgroup kernels hold
+int wgm_capacity();  // largest N of the multi-pick single-workgroup kernel
+// In all FPS launchers `start_dev`, when not null, is a device array with one
+// start index per cloud that overrides `start` (read by the kernel).
+// `max_picks` caps the picks one pass over the points may deliver (0: no cap
+// beyond kMaxPicksPerRound); the result does not depend on it.  status[1]
+// receives the largest number of passes any cloud took (multi-pick kernel only).
+hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, const int *start_dev,
+                         int32_t *idx, long idx_stride, float *md, long md_stride, int max_picks,
+                         int *status, hipStream_t s);
+
+// ---- fps_grid.hip: clouds spread over the whole device, resident in registers ----
+constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a launch may use
 size_t grid_exchange_bytes_per_cloud();  // bytes of one cloud's exchange area (two record buffers)
 long grid_capacity(int num_cu);          // largest N the register-resident grid kernel holds
 // How B clouds of N points are laid over the device: workgroups per cloud, and

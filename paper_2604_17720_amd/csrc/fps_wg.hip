@@ -7,8 +7,7 @@
 // per-lane argmax, a DPP max across the wave, one LDS exchange across waves
 // (double-buffered, so a single s_barrier per pick).  Nothing is re-read from
 // HBM after the initial load.
-#include "fps_device.h"
-#include "fps_launch.h"
+#include "fps_exchange.h"
 
 namespace ffps {
 
@@ -123,19 +122,252 @@ static hipError_t launch_wg_t(const float *xyz, int B, int N, int M, int start, 
     return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------
+// k_fps_wgm: one workgroup per cloud, MANY picks per pass over the points.
+//
+// The workgroup is one REPLAY wave (wave 0) plus NWK worker waves that own the
+// points (point i belongs to worker lane i mod NTW); waves 4, 8, 12 exit at
+// once so that the replay wave has its SIMD to itself.  Per round every worker
+// lane reports the two best of its own points and the value of its third best
+// (one 16-byte LDS record); the replay wave takes the 2 * NTW reported points as
+// candidates and replays the greedy rule of Eq. 1 on them alone (fps_exchange.h)
+// for as long as the best candidate stays strictly above every lane's
+// third-best value, since no unreported point can then be the maximum.  Picks go to the
+// workers through LDS one by one while the replay is still running.  A round
+// delivers about (6 NTW^2)^(1/3) picks, so the workgroup-wide reduction of the
+// one-pick loop is paid once per ~60 picks instead of once per pick.
+struct WgmArgs {
+    const float *xyz;
+    int N, M, start;
+    const int *start_dev;
+    int32_t *idx_out;
+    long idx_stride;
+    float *md_out;
+    long md_stride;
+    int max_picks;
+    int *status;  // status[1] receives the largest number of rounds any cloud took
+};
+
+__host__ __device__ constexpr int wgm_waves(int nwk) { return nwk + nwk / 3; }
+
+template <int NWK, int P>
+__global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
+    static_assert(NWK % 3 == 0 && NWK >= 3 && NWK <= 6, "worker waves come in threes");
+    constexpr int NTW = NWK * kWave;  // worker lanes = reporting units
+    constexpr int KR = NWK;           // records per lane of the replay wave
+    constexpr int KC = 2 * KR;        // candidates per lane of the replay wave
+    __shared__ float4 sxyz[NTW * P];  // coordinates by point index
+    __shared__ u32x4 rec[NTW];        // {best value, second value, third value, j1 | j2 << 16}
+    __shared__ RoundLds L;
+    // {batch id, picks emitted in total once that batch is complete}, one 8-byte word
+    __shared__ __attribute__((aligned(8))) uint32_t fin[2];
+
+    const int cloud = blockIdx.x;
+    a.xyz += (size_t)cloud * a.N * 3;
+    a.idx_out += cloud * a.idx_stride;
+    if (a.md_out) a.md_out += cloud * a.md_stride;
+    if (a.start_dev) a.start = a.start_dev[cloud];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    if (wave != 0 && (wave & 3) == 0) return;  // leaves the replay wave's SIMD to it
+
+    const uint32_t pk_off = lds_offset(L.pk);
+    const uint32_t fin_off = lds_offset(fin);
+
+    if (wave == 0) {
+        // batch 0 is the seed point alone; other slots start with an impossible seq
+        u32x4 s;
+        s.x = f2u(a.xyz[3 * (size_t)a.start + 0]);
+        s.y = f2u(a.xyz[3 * (size_t)a.start + 1]);
+        s.z = f2u(a.xyz[3 * (size_t)a.start + 2]);
+        for (int c = lane; c < kMaxPicksPerRound; c += kWave) {
+            s.w = c == 0 ? 0u : 0xffffffffu;
+            lds_write16(pk_off + c * 16, s);
+        }
+        if (lane == 0) {
+            u32x2 f;
+            f.x = 0u; f.y = 1u;
+            lds_write8(fin_off, f);
+            a.idx_out[0] = a.start;
+            if (a.md_out) a.md_out[0] = __builtin_inff();
+        }
+    }
+
+    if (wave != 0) {
+        // =============================== worker ===============================
+        const int wk = wave - 1 - wave / 4;  // 0 .. NWK-1
+        const int t = wk * kWave + lane;      // worker lane number
+        // element j of this lane is point j * NTW + t: ascending in j
+        float x[P], y[P], z[P], m[P];
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+            const int i = j * NTW + t;
+            const bool ok = i < a.N;
+            x[j] = ok ? a.xyz[3 * (size_t)i + 0] : 0.f;
+            y[j] = ok ? a.xyz[3 * (size_t)i + 1] : 0.f;
+            z[j] = ok ? a.xyz[3 * (size_t)i + 2] : 0.f;
+            // padding: value 0 and an index beyond every real one, never preferred
+            m[j] = ok ? __builtin_inff() : 0.f;
+            sxyz[i] = make_float4(x[j], y[j], z[j], 0.f);
+        }
+        __syncthreads();  // pick slots and coordinates in place
+        int applied = 0;  // picks applied so far = sequence number of the next pick
+        for (int batch = 0;; ++batch) {
+            // ---- take this batch's picks from LDS as they appear; the read of the
+            //      next slot is in flight while the current pick is applied ----
+            const int batch_base = applied;
+            u32x4 slot = lds_read16(pk_off);
+            while (true) {
+                // every lane read the same slot: the sequence number is wave-uniform
+                if (__builtin_amdgcn_readfirstlane((int)slot.w) == applied) {
+                    const float lx = u2f(slot.x), ly = u2f(slot.y), lz = u2f(slot.z);
+                    ++applied;
+                    const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
+                    lds_issue16(slot, pk_off + pos * 16);
+#pragma unroll
+                    for (int j = 0; j < P; ++j) {
+                        // distances are >= +0: the smaller bit pattern is the smaller value
+                        const uint32_t d = f2u(sqdist(x[j], y[j], z[j], lx, ly, lz));
+                        m[j] = u2f(d < f2u(m[j]) ? d : f2u(m[j]));
+                    }
+                    lds_wait16(slot);
+                } else {
+                    const u32x2 f = lds_read8(fin_off);
+                    if (__builtin_amdgcn_readfirstlane((int)f.x) == batch &&
+                        applied >= __builtin_amdgcn_readfirstlane((int)f.y))
+                        break;
+                    __builtin_amdgcn_s_sleep(1);
+                    const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
+                    slot = lds_read16(pk_off + pos * 16);
+                }
+            }
+            if (applied >= a.M) break;
+            // ---- the lane's top three values (element numbers for the first two) ----
+            float a1 = m[0], a2 = 0.f, a3 = 0.f;
+            int j1 = 0, j2 = 0;
+#pragma unroll
+            for (int j = 1; j < P; ++j) {
+                float v = m[j];
+                bool g1 = v > a1, g2 = v > a2;  // strict: the earlier (lower) j keeps a tie
+                a3 = fmaxf(a3, fminf(v, a2));
+                j2 = g1 ? j1 : (g2 ? j : j2);
+                a2 = fmaxf(a2, fminf(v, a1));
+                j1 = g1 ? j : j1;
+                a1 = fmaxf(a1, v);
+            }
+            u32x4 r;
+            r.x = f2u(a1); r.y = f2u(a2); r.z = f2u(a3);
+            r.w = (uint32_t)j1 | ((uint32_t)j2 << 16);
+            rec[t] = r;
+            __syncthreads();  // records ready for the replay wave
+        }
+        return;
+    }
+
+    // ============================== replay wave ==============================
+    __syncthreads();  // coordinates in place
+    int npicked = 1;
+    int round = 0;
+    RoundProf *prof = nullptr;
+#ifdef FFPS_PROFILE
+    RoundProf prof_store = {};
+    if (cloud == 0) prof = &prof_store;
+    prof_store.last = wall_clock64();
+    const uint64_t prof_w0 = prof_store.last, prof_c0 = clock64();
+#endif
+    while (npicked < a.M) {
+        ++round;
+        FFPS_STAMP(prof, 0);
+        __syncthreads();  // workers have applied every pick so far and written rec
+        FFPS_STAMP(prof, 1);
+        uint32_t cv[KC], ci[KC], lb = 0u;
+        float cx[KC], cy[KC], cz[KC];
+#pragma unroll
+        for (int q = 0; q < KR; ++q) {
+            const int t = q * kWave + lane;
+            const u32x4 r = rec[t];
+            cv[2 * q] = r.x;
+            cv[2 * q + 1] = r.y;
+            lb = umax(lb, r.z);
+            ci[2 * q] = (r.w & 0xffffu) * NTW + t;
+            ci[2 * q + 1] = (r.w >> 16) * NTW + t;
+        }
+#pragma unroll
+        for (int c = 0; c < KC; ++c) {
+            const float4 v = sxyz[ci[c]];
+            cx[c] = v.x; cy[c] = v.y; cz[c] = v.z;
+        }
+        const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
+        FFPS_STAMP(prof, 2);
+        const int cnt = replay_round<KC>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
+        for (int c = lane; c < cnt; c += kWave) {
+            a.idx_out[npicked + c] = (int32_t)L.pk_idx[c];
+            if (a.md_out) a.md_out[npicked + c] = u2f(L.pk_val[c]);
+        }
+        npicked += cnt;
+        if (lane == 0) {
+            u32x2 f;
+            f.x = (uint32_t)round; f.y = (uint32_t)npicked;
+            lds_write8(fin_off, f);
+        }
+        FFPS_STAMP(prof, 4);
+    }
+    if (lane == 0) {
+        __hip_atomic_fetch_max(a.status + 1, round, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#ifdef FFPS_PROFILE
+        if (cloud == 0) {
+            for (int i = 0; i < 8; ++i) a.status[8 + i] = (int)prof_store.acc[i];
+            for (int i = 0; i < 4; ++i) a.status[20 + i] = (int)prof_store.loop[i];
+            for (int i = 0; i < 4; ++i) a.status[24 + i] = (int)prof_store.sub[i];
+            a.status[16] = (int)(wall_clock64() - prof_w0);    // 10 ns units
+            a.status[17] = (int)((clock64() - prof_c0) >> 4);  // shader cycles / 16
+        }
+#endif
+    }
+}
+
+template <int NWK, int P>
+static hipError_t launch_wgm_t(const WgmArgs &a, int B, hipStream_t s) {
+    hipLaunchKernelGGL((k_fps_wgm<NWK, P>), dim3(B), dim3(kWave * wgm_waves(NWK)), 0, s, a);
+    return hipGetLastError();
+}
+
 int wg_capacity() { return 1024 * 24; }
 
+int wgm_capacity() { return 6 * kWave * 12; }
+
+// Very small clouds (one wave holds them) and clouds beyond the multi-pick
+// kernel's capacity use the one-pick kernel, the others the multi-pick kernel.
 // Shapes are ordered by capacity; the first one that holds N is used.
 hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, const int *start_dev,
-                         int32_t *idx, long idx_stride, float *md, long md_stride, hipStream_t s) {
-#define FFPS_WG_CASE(NT, P)         \
-    if (N <= (NT) * (P))            \
+                         int32_t *idx, long idx_stride, float *md, long md_stride, int max_picks,
+                         int *status, hipStream_t s) {
+#define FFPS_WG_CASE(NT, P) \
+    if (N <= (NT) * (P))    \
         return launch_wg_t<NT, P>(xyz, B, N, M, start, start_dev, idx, idx_stride, md, md_stride, s);
     FFPS_WG_CASE(64, 4)
-    FFPS_WG_CASE(256, 2)
-    FFPS_WG_CASE(256, 4)
-    FFPS_WG_CASE(256, 8)
-    FFPS_WG_CASE(256, 16)
+    if (N <= wgm_capacity()) {
+        WgmArgs a;
+        a.xyz = xyz; a.N = N; a.M = M; a.start = start; a.start_dev = start_dev;
+        a.idx_out = idx; a.idx_stride = idx_stride;
+        a.md_out = md; a.md_stride = md_stride;
+        a.status = status;
+        a.max_picks = max_picks < 1 ? kMaxPicksPerRound
+                                    : (max_picks > kMaxPicksPerRound ? kMaxPicksPerRound : max_picks);
+#define FFPS_WGM_CASE(NWK, P) \
+    if (N <= (NWK) * kWave * (P)) return launch_wgm_t<NWK, P>(a, B, s);
+        // one worker wave per SIMD up to 1152 points, two beyond
+        FFPS_WGM_CASE(3, 2)
+        FFPS_WGM_CASE(3, 4)
+        FFPS_WGM_CASE(3, 6)
+        FFPS_WGM_CASE(6, 4)
+        FFPS_WGM_CASE(6, 6)
+        FFPS_WGM_CASE(6, 8)
+        FFPS_WGM_CASE(6, 12)
+#undef FFPS_WGM_CASE
+    }
     FFPS_WG_CASE(1024, 8)
     FFPS_WG_CASE(1024, 16)
     FFPS_WG_CASE(1024, 24)

@@ -98,6 +98,33 @@ def test_grid_multi_point_per_lane(fb, oracle, n, m):
     _check_exact(fb, oracle, x, m, 17, GRID)
 
 
+@pytest.mark.parametrize("b,n,m", [
+    (3, 256, 256), (3, 257, 257), (2, 384, 200), (2, 385, 385), (5, 768, 300), (2, 769, 500),
+    (33, 1152, 200), (2, 1153, 700), (2, 1536, 900), (2, 1537, 300), (2, 2304, 1200),
+    (2, 2305, 400), (2, 3072, 700), (2, 3073, 300), (2, 4608, 2500), (2, 4609, 300),
+    (2, 8192, 300), (2, 8193, 200),
+])
+def test_single_workgroup_kernel_shapes(fb, oracle, b, n, m):
+    """Every shape of the one-workgroup-per-cloud kernels, at its capacity and one
+    point past it (which selects the next shape), on surface-like clouds."""
+    x = np.stack([inputs.shape_cloud(n, 52000 + 7 * n + i) for i in range(b)])
+    _check_exact(fb, oracle, x, m, n // 3, WG)
+
+
+def test_single_workgroup_picks_per_pass_do_not_change_the_result(fb, oracle):
+    x = np.stack([inputs.planes_and_clusters(3000, 91000 + i) for i in range(3)])
+    ref = oracle.fps_exact(x, 1000, 0)
+    rounds = {}
+    for picks in (1, 2, 7, 33, 64, 128):
+        print(f"picks={picks}", flush=True)
+        ws = fb.make_workspace(3, 3000, 1000)
+        got = fb.ffps_exact(_dev(x), 1000, 0, fb.variant_with_picks(WG, picks), workspace=ws)
+        assert np.array_equal(got.cpu().numpy(), ref)
+        rounds[picks] = fb.ffps_last_rounds(ws)
+    assert rounds[1] == 999            # one pick per pass: as many passes as picks
+    assert rounds[128] < rounds[7] < rounds[1]
+
+
 @pytest.mark.parametrize("cloud", ["line", "grid2", "grid3", "dups"])
 @pytest.mark.parametrize("variant", [WG, GRID, STREAM])
 def test_ties_and_duplicates(fb, oracle, variant, cloud):
