@@ -91,11 +91,10 @@ int clear_exchange(char *ws, const Workspace &w, int clouds, hipStream_t s) {
 int resolve_variant(int B, int N, int variant, const Device &dev) {
     int v = variant_kind(variant);
     if (v == FFPS_VARIANT_AUTO) {
-        // Small clouds, or so many clouds that each would get only a few workgroups:
-        // one workgroup per cloud.  Otherwise clusters of workgroups per cloud.
-        const bool fits_wg = N <= wg_capacity();
-        const bool fits_grid = N <= grid_capacity(dev.num_cu);
-        if (fits_wg && (N <= wgm_capacity() || !fits_grid || plan_fps_grid(B, N, dev.num_cu).wg_per_cloud < 16))
+        // Clouds that fit the multi-pick single-workgroup kernel run there, larger
+        // ones on clusters of workgroups, those beyond the registers of the
+        // device are streamed.
+        if (N <= wgm_capacity())
             v = FFPS_VARIANT_WG;
         else if (N <= grid_capacity(dev.num_cu))
             v = FFPS_VARIANT_GRID;

@@ -1,23 +1,25 @@
 // Cross-workgroup exchange and candidate replay shared by the multi-workgroup
 // FPS kernels (register-resident and HBM-streaming).
 //
-// Once per ROUND every workgroup contributes its two best points and an upper
-// bound on all its other points (its third-best value).  One wave per workgroup
-// publishes them as four 16-byte chunks, each closed by a checksum that also
-// encodes the round, gathers the chunks of all G workgroups with coalesced
+// The points of a cloud are divided among U <= 256 reporting UNITS (a whole
+// workgroup, or each worker wave of a workgroup).  Once per ROUND every unit
+// contributes its two best points and an upper bound on all its other points
+// (its third-best value).  One wave per workgroup publishes the records of its
+// units as four 16-byte chunks each, every chunk closed by a checksum that also
+// encodes the round, gathers the chunks of all U units with coalesced
 // device-scope loads (the only cross-workgroup step: no counters, no fences, no
-// separate barrier), and replays the greedy rule of Eq. 1 on the 2G published
+// separate barrier), and replays the greedy rule of Eq. 1 on the 2U published
 // candidates: the best candidate is the next pick as long as its value is
 // strictly above B = max of all bounds, because no unpublished point can then
 // reach it; picking it lowers the other candidates' values by the same distance
 // rule, and the replay continues until the test fails.  The first pick of a
 // round never needs the test: the global best point (largest value, lowest
-// index among equals) is the best of its own workgroup, hence published.
+// index among equals) is the best of its own unit, hence published.
 // Every workgroup replays the same arithmetic on the same records, so all agree
 // on the picks without further communication.
 //
 // "Best" always means largest value, then lowest point index.  Points may be
-// assigned to workgroups in any way; candidates carry their indices, and equal
+// assigned to units in any way; candidates carry their indices, and equal
 // values are detected and resolved on the index wherever they can occur.
 #pragma once
 #include "fps_device.h"
@@ -25,7 +27,8 @@
 
 namespace ffps {
 
-constexpr int kRPL = kMaxGridWG / kWave;  // workgroup records per lane of the gathering wave
+constexpr int kMaxUnits = kMaxGridWG;     // reporting units of a cloud
+constexpr int kRPL = kMaxUnits / kWave;   // unit records per lane of the gathering wave
 constexpr int kCPL = 2 * kRPL;            // candidates per lane before compaction
 constexpr int kSpinLimit = 1 << 19;
 constexpr uint32_t kNoIndex = 0x7fffffffu;  // index of a candidate that does not exist
@@ -34,13 +37,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Exchange area: two buffers (round parity); each holds four chunk arrays
 // (A: {v_a, v_b, bound, check}, B: {x_a, y_a, z_a, check}, C: {x_b, y_b, z_b,
-// check}, D: {i_a, i_b, 0, check}) of 256 slots x 16 bytes.  Workgroup w uses
-// slot (w & 3) * 64 + (w >> 2), so that a wave reading slot q*64 + lane with one
-// 16-byte load per lane touches one contiguous KiB.
+// check}, D: {i_a, i_b, 0, check}) of 256 slots x 16 bytes.  Unit u uses slot
+// u, and lane L of a gathering wave reads slots L, L + 64, L + 128, L + 192: each
+// 16-byte load per lane touches one contiguous KiB, and units with consecutive
+// numbers, which hold consecutive point indices, land in different lanes.
 constexpr int kChunks = 4;
-constexpr size_t kChunkBytes = (size_t)kMaxGridWG * 16;
+constexpr size_t kChunkBytes = (size_t)kMaxUnits * 16;
 constexpr size_t kBufBytes = kChunks * kChunkBytes;
-__device__ __forceinline__ int slot_of(int w) { return (w & 3) * kWave + (w >> 2); }
 
 // A chunk is valid for a round when its last word equals this value.  Memory
 // cleared to zero never validates (the round term is non-zero for round >= 1),
@@ -446,19 +449,22 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
     return cnt;
 }
 
-// One round, run by ONE full wave of workgroup w.  Publishes `in`, gathers all
-// G records, replays, writes each pick as {x, y, z, npicked + c} to L.pk[c]
+// One round, run by ONE full wave of a workgroup.  The cloud has U reporting
+// units (a whole workgroup, or each of its worker waves); lanes 0 .. nsub-1 of
+// this wave publish `in` as unit unit0 + lane.  The wave then gathers all U
+// records, replays, writes each pick as {x, y, z, npicked + c} to L.pk[c]
 // (16-byte LDS writes, in pick order, so other waves may consume them while
-// the replay is still running); workgroup 0 records the picks in idx_out /
-// md_out.  Returns the number of picks of the round (1 .. cap), or -1 after
-// setting *status when another workgroup's record never arrived.
-__device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G, int w, int lane,
-                                              uint32_t round, const RoundInput &in, int npicked,
-                                              int cap, int32_t *idx_out, float *md_out, int *status,
+// the replay is still running); the wave with `writer` set records the picks in
+// idx_out / md_out.  Returns the number of picks of the round (1 .. cap), or -1
+// after setting *status when another unit's record never arrived.
+__device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int U, int unit0, int nsub,
+                                              bool writer, int lane, uint32_t round,
+                                              const RoundInput &in, int npicked, int cap,
+                                              int32_t *idx_out, float *md_out, int *status,
                                               RoundProf *prof) {
     // ---- publish ----
     char *buf = exchange + (size_t)(round & 1) * kBufBytes;
-    if (lane == 0) {
+    if (lane < nsub) {
         u32x4 c0, c1, c2, c3;
         c0.x = in.va; c0.y = in.vb; c0.z = in.bound;
         c0.w = chunk_check(c0.x, c0.y, c0.z, round, 0);
@@ -468,14 +474,14 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
         c2.w = chunk_check(c2.x, c2.y, c2.z, round, 2);
         c3.x = in.ia; c3.y = in.ib; c3.z = 0u;
         c3.w = chunk_check(c3.x, c3.y, c3.z, round, 3);
-        const size_t so = (size_t)slot_of(w) * 16;
+        const size_t so = (size_t)(unit0 + lane) * 16;
         store_chunk(buf + so, c0);
         store_chunk(buf + kChunkBytes + so, c1);
         store_chunk(buf + 2 * kChunkBytes + so, c2);
         store_chunk(buf + 3 * kChunkBytes + so, c3);
     }
     FFPS_STAMP(prof, 2);
-    // ---- gather: lane L reads slots q*64+L = workgroups 4L+q ----
+    // ---- gather: lane L reads slots (= units) q*64+L ----
     u32x4 ra[kRPL], rb[kRPL], rc[kRPL], rd[kRPL];
     bool gave_up = false;
     for (int spin = 0;; ++spin) {
@@ -486,7 +492,7 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
         for (int q = 0; q < kRPL; ++q) {
             bool ok = chunk_ok(ra[q], round, 0) && chunk_ok(rb[q], round, 1) &&
                       chunk_ok(rc[q], round, 2) && chunk_ok(rd[q], round, 3);
-            all = all && (ok || lane * kRPL + q >= G);
+            all = all && (ok || q * kWave + lane >= U);
         }
 #ifdef FFPS_PROFILE
         if (prof) ++prof->acc[7];
@@ -502,12 +508,12 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
         if (lane == 0) __hip_atomic_store(status, -5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return -1;
     }
-    // candidate c = 2q + r of this lane: workgroup 4*lane + q, its r-th entry
+    // candidate c = 2q + r of this lane: unit q*64 + lane, its r-th entry
     uint32_t cv[kCPL], ci[kCPL], lb = 0u;
     float cx[kCPL], cy[kCPL], cz[kCPL];
 #pragma unroll
     for (int q = 0; q < kRPL; ++q) {
-        const bool present = lane * kRPL + q < G;  // absent records: value 0, bound 0
+        const bool present = q * kWave + lane < U;  // absent records: value 0, bound 0
         cv[2 * q] = present ? ra[q].x : 0u;
         cv[2 * q + 1] = present ? ra[q].y : 0u;
         lb = umax(lb, present ? ra[q].z : 0u);
@@ -517,8 +523,8 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int G
         cx[2 * q + 1] = u2f(rc[q].x); cy[2 * q + 1] = u2f(rc[q].y); cz[2 * q + 1] = u2f(rc[q].z);
     }
     const int cnt = replay_round<kCPL>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
-    // workgroup 0 records the picks (the same wave wrote pk_idx / pk_val)
-    if (w == 0) {
+    // one workgroup records the picks (the same wave wrote pk_idx / pk_val)
+    if (writer) {
         for (int c = lane; c < cnt; c += kWave) {
             idx_out[npicked + c] = (int32_t)L.pk_idx[c];
             if (md_out) md_out[npicked + c] = u2f(L.pk_val[c]);

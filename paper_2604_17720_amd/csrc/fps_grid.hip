@@ -39,6 +39,7 @@ struct GridArgs {  // pointers are those of the first cloud of the launch
     int N, M, start;
     const int *start_dev;  // per-cloud start indices overriding `start`, or null
     int wg_per_cloud;  // the grid holds (clouds of this launch) x wg_per_cloud workgroups
+    int wave_units;    // 1: every worker wave reports on its own; 0: the workgroup reports as one
     int32_t *idx_out;
     long idx_stride;   // elements between the outputs of consecutive clouds
     float *md_out;
@@ -57,7 +58,8 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
     static_assert(NWK % 3 == 0 && NWK >= 3 && NWK <= 12, "worker waves come in threes");
     __shared__ WaveTop wtop[NWK];
     __shared__ RoundLds L;
-    __shared__ int fin[2];  // {batch id, picks emitted in total once that batch is complete}
+    // {batch id, picks emitted in total once that batch is complete}, one 8-byte word
+    __shared__ __attribute__((aligned(8))) uint32_t fin[2];
     __shared__ int s_abort;
 
     // A launch may carry several clouds: each gets a cluster of wg_per_cloud
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
     // 16-byte LDS word {x, y, z, seq}: written and read by one instruction each, so
     // a reader that sees the expected seq also sees its coordinates.
     const uint32_t pk_off = lds_offset(L.pk);
-    volatile int *vfin = fin;
+    const uint32_t fin_off = lds_offset(fin);
 
     if (wave == 0) {
         // batch 0 is the seed point alone; other slots start with an impossible seq
@@ -93,8 +95,9 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             lds_write16(pk_off + c * 16, s);
         }
         if (lane == 0) {
-            vfin[1] = 1;
-            vfin[0] = 0;
+            u32x2 f;
+            f.x = 0u; f.y = 1u;
+            lds_write8(fin_off, f);
             s_abort = 0;
             if (w == 0) {
                 a.idx_out[0] = a.start;
@@ -124,22 +127,29 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         }
         int applied = 0;  // picks applied so far = sequence number of the next pick
         for (int batch = 0;; ++batch) {
-            // ---- 1a. take this batch's picks from LDS as they appear ----
+            // ---- 1a. take this batch's picks from LDS as they appear; the read of
+            //      the next slot is in flight while the current pick is applied ----
             const int batch_base = applied;
+            u32x4 slot = lds_read16(pk_off);
             while (true) {
-                const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
-                const u32x4 slot = lds_read16(pk_off + pos * 16);
-                if ((int)slot.w == applied) {
+                // every lane read the same slot: the sequence number is wave-uniform
+                if (__builtin_amdgcn_readfirstlane((int)slot.w) == applied) {
                     const float lx = u2f(slot.x), ly = u2f(slot.y), lz = u2f(slot.z);
                     ++applied;
+                    const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
+                    lds_issue16(slot, pk_off + pos * 16);
 #pragma unroll
                     for (int j = 0; j < P; ++j)
                         m[j] = fminf(m[j], sqdist(x[j], y[j], z[j], lx, ly, lz));
+                    lds_wait16(slot);
                 } else {
-                    int fb = vfin[0];  // batch id first, then the total it vouches for
-                    int ft = vfin[1];
-                    if (fb == batch && applied >= ft) break;
+                    const u32x2 f = lds_read8(fin_off);
+                    if (__builtin_amdgcn_readfirstlane((int)f.x) == batch &&
+                        applied >= __builtin_amdgcn_readfirstlane((int)f.y))
+                        break;
                     __builtin_amdgcn_s_sleep(1);
+                    const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
+                    slot = lds_read16(pk_off + pos * 16);
                 }
             }
             if (s_abort || applied >= a.M) break;
@@ -195,37 +205,52 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         FFPS_STAMP(prof, 0);
         __syncthreads();  // workers have applied every pick so far and filled wtop
         FFPS_STAMP(prof, 1);
-        // ---- 2a. workgroup top two + bound from the worker waves' triples ----
-        const bool act = lane < NWK;
-        int w1, w2;
-        bool s2w;
-        const Top3 g3 = merge_top3(wtop[act ? lane : 0].t, act, lane,
-                                   [](uint32_t v) { return row_max_uniform(v); },
-                                   [](uint32_t v) { return row_min_uniform(v); }, w1, w2, s2w);
-        // candidate a = wave w1's first; candidate b = wave w2's first, or w1's second
         RoundInput in;
-        in.va = g3.v1; in.vb = g3.v2; in.bound = g3.v3;
-        in.ia = g3.i1; in.ib = g3.i2;
-        in.xa = wtop[w1].x1; in.ya = wtop[w1].y1; in.za = wtop[w1].z1;
-        in.xb = s2w ? wtop[w1].x2 : wtop[w2].x1;
-        in.yb = s2w ? wtop[w1].y2 : wtop[w2].y1;
-        in.zb = s2w ? wtop[w1].z2 : wtop[w2].z1;
-        // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
+        int cnt;
         const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
-        const int cnt = exchange_round(L, a.exchange, G, w, lane, round, in, npicked, cap, a.idx_out,
-                                       a.md_out, a.status, prof);
+        if (a.wave_units) {
+            // ---- 2a. every worker wave is a unit of its own: lane s reports wave s ----
+            const WaveTop &o = wtop[lane < NWK ? lane : 0];
+            in.va = o.t.v1; in.vb = o.t.v2; in.bound = o.t.v3;
+            in.ia = o.t.i1; in.ib = o.t.i2;
+            in.xa = o.x1; in.ya = o.y1; in.za = o.z1;
+            in.xb = o.x2; in.yb = o.y2; in.zb = o.z2;
+            // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
+            cnt = exchange_round(L, a.exchange, G * NWK, w * NWK, NWK, w == 0, lane, round, in,
+                                 npicked, cap, a.idx_out, a.md_out, a.status, prof);
+        } else {
+            // ---- 2a. workgroup top two + bound from the worker waves' triples ----
+            const bool act = lane < NWK;
+            int w1, w2;
+            bool s2w;
+            const Top3 g3 = merge_top3(wtop[act ? lane : 0].t, act, lane,
+                                       [](uint32_t v) { return row_max_uniform(v); },
+                                       [](uint32_t v) { return row_min_uniform(v); }, w1, w2, s2w);
+            // candidate a = wave w1's first; candidate b = wave w2's first, or w1's second
+            in.va = g3.v1; in.vb = g3.v2; in.bound = g3.v3;
+            in.ia = g3.i1; in.ib = g3.i2;
+            in.xa = wtop[w1].x1; in.ya = wtop[w1].y1; in.za = wtop[w1].z1;
+            in.xb = s2w ? wtop[w1].x2 : wtop[w2].x1;
+            in.yb = s2w ? wtop[w1].y2 : wtop[w2].y1;
+            in.zb = s2w ? wtop[w1].z2 : wtop[w2].z1;
+            // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
+            cnt = exchange_round(L, a.exchange, G, w, 1, w == 0, lane, round, in, npicked, cap,
+                                 a.idx_out, a.md_out, a.status, prof);
+        }
         if (cnt < 0) {
             if (lane == 0) {
                 s_abort = 1;
-                vfin[1] = 0;
-                vfin[0] = (int)round;  // releases the workers, which then see s_abort
+                u32x2 f;
+                f.x = round; f.y = 0u;
+                lds_write8(fin_off, f);  // releases the workers, which then see s_abort
             }
             return;
         }
         npicked += cnt;
         if (lane == 0) {
-            vfin[1] = npicked;  // total first, then the batch id that vouches for it
-            vfin[0] = (int)round;
+            u32x2 f;
+            f.x = round; f.y = (uint32_t)npicked;
+            lds_write8(fin_off, f);
         }
         FFPS_STAMP(prof, 4);
     }
@@ -249,7 +274,29 @@ hipError_t launch_t(GridArgs &a, int num_wg, hipStream_t s) {
                                       dim3(kWave * grid_waves(NWK)), params, 0, s);
 }
 
+// Kernel shapes (worker waves, points per worker lane), ordered by capacity; a
+// workgroup's slice runs on the first shape that holds it.  One worker wave per
+// SIMD for small slices, two from 385 points per workgroup on.
+#define FFPS_GRID_SHAPES(X) \
+    X(3, 1) X(3, 2) X(6, 2) X(6, 3) X(6, 4) X(6, 5) X(6, 6) X(6, 8) X(12, 6) X(12, 8) X(12, 12) X(12, 16)
+
 constexpr int kMaxPointsPerWG = 12 * kWave * 16;
+
+// Worker waves of the shape that holds per_wg points (0 if none does).
+int shape_waves(int per_wg) {
+#define X(NWK, P) \
+    if (per_wg <= (NWK) * kWave * (P)) return NWK;
+    FFPS_GRID_SHAPES(X)
+#undef X
+    return 0;
+}
+
+// Reporting units of a cloud on g workgroups: every worker wave when that many
+// records fit the exchange area, else one per workgroup.
+int units_of(int N, int g) {
+    const int nwk = shape_waves((N + g - 1) / g);
+    return nwk > 0 && g * nwk <= kMaxUnits ? g * nwk : g;
+}
 
 }  // namespace
 
@@ -275,9 +322,20 @@ GridPlan plan_fps_grid(int B, int N, int num_cu) {
     int g = want < share ? want : share;
     const int need = (N + kMaxPointsPerWG - 1) / kMaxPointsPerWG;  // registers must hold the cloud
     if (g < need) g = need;
+    // The picks a round delivers grow with the number of reporting units, and
+    // fewer workgroups whose waves report one by one can give more units than
+    // many workgroups that report as a whole: take the count with the most units.
+    int best = g, best_units = units_of(N, g);
+    for (int c = g - 1; c >= need && c >= 1; --c) {
+        const int u = units_of(N, c);
+        if (u > best_units) {
+            best = c;
+            best_units = u;
+        }
+    }
     GridPlan p;
-    p.wg_per_cloud = g;
-    p.clouds_per_launch = maxG / g < 1 ? 1 : maxG / g;
+    p.wg_per_cloud = best;
+    p.clouds_per_launch = maxG / best < 1 ? 1 : maxG / best;
     if (p.clouds_per_launch > B) p.clouds_per_launch = B;
     return p;
 }
@@ -296,22 +354,11 @@ hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start
     a.max_picks = max_picks < 1 ? 1 : (max_picks > kMaxPicksPerRound ? kMaxPicksPerRound : max_picks);
     const int per_wg = (N + G - 1) / G;  // most points any workgroup holds
     const int num_wg = clouds * G;
-#define FFPS_GRID_CASE(NWK, P) \
+    a.wave_units = units_of(N, G) > G ? 1 : 0;
+#define X(NWK, P) \
     if (per_wg <= (NWK) * kWave * (P)) return launch_t<NWK, P>(a, num_wg, s);
-    // one worker wave per SIMD for small slices, two from 385 points per workgroup on
-    FFPS_GRID_CASE(3, 1)
-    FFPS_GRID_CASE(3, 2)
-    FFPS_GRID_CASE(6, 2)
-    FFPS_GRID_CASE(6, 3)
-    FFPS_GRID_CASE(6, 4)
-    FFPS_GRID_CASE(6, 5)
-    FFPS_GRID_CASE(6, 6)
-    FFPS_GRID_CASE(6, 8)
-    FFPS_GRID_CASE(12, 6)
-    FFPS_GRID_CASE(12, 8)
-    FFPS_GRID_CASE(12, 12)
-    FFPS_GRID_CASE(12, 16)
-#undef FFPS_GRID_CASE
+    FFPS_GRID_SHAPES(X)
+#undef X
     return hipErrorInvalidValue;
 }
 

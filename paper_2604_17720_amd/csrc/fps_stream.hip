@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
             in.yb = eb ? a.xyz[3 * (size_t)(eb ? ib : 0) + 1] : 0.f;
             in.zb = eb ? a.xyz[3 * (size_t)(eb ? ib : 0) + 2] : 0.f;
             const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
-            const int cnt = exchange_round(L, a.exchange, G, w, lane, round, in, npicked, cap,
+            const int cnt = exchange_round(L, a.exchange, G, w, 1, w == 0, lane, round, in, npicked, cap,
                                            a.idx_out, a.md_out, a.status, nullptr);
             if (lane == 0) {
                 s_cnt = cnt < 0 ? 0 : cnt;
