@@ -188,6 +188,8 @@ struct RoundLds {
     __attribute__((aligned(16))) u32x4 pk[kMaxPicksPerRound];  // picks of the round: {x, y, z, seq}
     uint32_t pk_idx[kMaxPicksPerRound];  // index of each pick of the round
     uint32_t pk_val[kMaxPicksPerRound];  // and the value it was picked with
+    uint32_t pk_key[kMaxPicksPerRound];  // winning key of each pick (packed replay loops)
+    uint32_t tab_idx[2 * kWave];         // point index by candidate code (packed replay loops)
     __attribute__((aligned(16))) u32x4 cmp_a[2 * kWave];  // compacted live candidates: {value, index, x, y}
     float cmp_z[2 * kWave];                               // and z
 };
@@ -340,31 +342,48 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
         }
         // the same wave wrote and now reads: LDS keeps its accesses in order
         FFPS_SUB(2);
+        // In both loops below the key of a candidate is (value - T) << 7 | code,
+        // where the 7-bit code names the candidate (its entry in L.tab_idx).  The
+        // wave-wide max K names a best candidate.  Another lane holds the same value
+        // exactly when its key differs from K in the code bits alone, i.e. when
+        // (key ^ K) - 1 < 127: one compare and a branch on the lane mask.  Each pick
+        // is handed over as {x, y, z, seq} by every lane at once (the data are
+        // wave-uniform, so no lane has to be singled out), and K itself is noted:
+        // it holds the pick's value and, through the code, its index.
+        auto hand_over = [&](int c, uint32_t K) {
+            u32x4 s;
+            s.x = f2u(px); s.y = f2u(py); s.z = f2u(pz); s.w = (uint32_t)(npicked + c);
+            lds_write16(pk_off + c * 16, s);
+            L.pk_key[c] = K;
+        };
         if (total <= kWave) {
-            // one candidate per lane: lane L takes position L
+            // one candidate per lane: lane L takes position L, code = L
             const bool h = lane < total;
             const u32x4 r0 = L.cmp_a[lane];
             uint32_t v0 = h ? r0.x : 0u;
             const uint32_t i0 = h ? r0.y : kNoIndex;
             const float x0 = h ? u2f(r0.z) : 0.f, y0 = h ? u2f(r0.w) : 0.f,
                         z0 = h ? L.cmp_z[lane] : 0.f;
+            L.tab_idx[lane] = i0;
 #ifdef FFPS_PROFILE
             const uint64_t lc0 = clock64();
 #endif
             while (true) {
-                const uint32_t key = (__builtin_elementwise_sub_sat(v0, T) << 7) | (uint32_t)lane;
-                const uint32_t K = wave_max_u32(key);
+                const uint32_t d = __builtin_elementwise_sub_sat(v0, T);
+                const uint32_t key = (d << 7) | (uint32_t)lane;
+                uint32_t K = wave_max_u32(key);
                 if ((K >> 7) == 0) break;  // cannot happen for the first pick
-                const uint64_t tied = __builtin_amdgcn_ballot_w64((key >> 7) == (K >> 7));
                 pl = (int)(K & 127u);
-                if (__builtin_popcountll(tied) > 1) {  // several candidates share the best value
-                    const uint32_t imin = wave_min_u32((key >> 7) == (K >> 7) ? i0 : 0xffffffffu);
-                    pl = first_lane((key >> 7) == (K >> 7) && i0 == imin);
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(((key ^ K) - 1u) < 127u) != 0, 0)) {
+                    // several candidates share the best value: the lowest index wins
+                    const uint32_t imin = wave_min_u32(d == (K >> 7) ? i0 : 0xffffffffu);
+                    pl = first_lane(d == (K >> 7) && i0 == imin);
+                    K = (K & ~127u) | (uint32_t)pl;
                 }
                 px = readlane_f(x0, pl);
                 py = readlane_f(y0, pl);
                 pz = readlane_f(z0, pl);
-                emit(lane == pl, cnt, i0, v0, x0, y0, z0);  // the winning lane hands over its own
+                hand_over(cnt, K);
                 if (++cnt >= cap) break;
                 v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
             }
@@ -376,7 +395,8 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
 #endif
         } else {
             // two candidates per lane (positions L and L + 64), the lower index first,
-            // so that a lane whose two values tie puts forward the right one
+            // so that a lane whose two values tie puts forward the right one;
+            // code = 2 L + (0 for the first, 1 for the second)
             const int p1 = lane + kWave;
             const bool h1 = p1 < total;  // position L itself is always taken here
             const u32x4 r0 = L.cmp_a[lane], r1 = L.cmp_a[p1];
@@ -393,6 +413,8 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
                 tf = y0; y0 = y1; y1 = tf;
                 tf = z0; z0 = z1; z1 = tf;
             }
+            L.tab_idx[2 * lane] = i0;
+            L.tab_idx[2 * lane + 1] = i1;
 #ifdef FFPS_PROFILE
             const uint64_t lc0 = clock64();
 #endif
@@ -401,20 +423,21 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
                 const uint32_t d1 = __builtin_elementwise_sub_sat(v1, T);
                 const bool sec = d1 > d0;  // strict: equal values put the lower index forward
                 const float bx = sec ? x1 : x0, by = sec ? y1 : y0, bz = sec ? z1 : z0;
-                const uint32_t bidx = sec ? i1 : i0;
-                const uint32_t key = ((sec ? d1 : d0) << 7) | (uint32_t)lane;
-                const uint32_t K = wave_max_u32(key);
+                const uint32_t bd = sec ? d1 : d0;
+                const uint32_t key = (bd << 7) | ((uint32_t)lane << 1) | (sec ? 1u : 0u);
+                uint32_t K = wave_max_u32(key);
                 if ((K >> 7) == 0) break;
-                const uint64_t tied = __builtin_amdgcn_ballot_w64((key >> 7) == (K >> 7));
-                pl = (int)(K & 127u);
-                if (__builtin_popcountll(tied) > 1) {
-                    const uint32_t imin = wave_min_u32((key >> 7) == (K >> 7) ? bidx : 0xffffffffu);
-                    pl = first_lane((key >> 7) == (K >> 7) && bidx == imin);
+                pl = (int)((K >> 1) & 63u);
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(((key ^ K) - 1u) < 127u) != 0, 0)) {
+                    const uint32_t bidx = sec ? i1 : i0;
+                    const uint32_t imin = wave_min_u32(bd == (K >> 7) ? bidx : 0xffffffffu);
+                    pl = first_lane(bd == (K >> 7) && bidx == imin);
+                    K = (K & ~127u) | (uint32_t)readlane_i((int)(key & 127u), pl);
                 }
                 px = readlane_f(bx, pl);
                 py = readlane_f(by, pl);
                 pz = readlane_f(bz, pl);
-                emit(lane == pl, cnt, bidx, sec ? v1 : v0, bx, by, bz);
+                hand_over(cnt, K);
                 if (++cnt >= cap) break;
                 v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
                 v1 = f2u(fminf(u2f(v1), sqdist(x1, y1, z1, px, py, pz)));
@@ -425,6 +448,12 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
                 prof->loop[3] += cnt;
             }
 #endif
+        }
+        // index and value of every pick from its noted key
+        for (int c = lane; c < cnt; c += kWave) {
+            const uint32_t K = L.pk_key[c];
+            L.pk_idx[c] = L.tab_idx[K & 127u];
+            L.pk_val[c] = (K >> 7) + T;
         }
     } else {
         // a single pick (best candidate not above the bound, or cap 1), or values
