@@ -53,12 +53,15 @@ __device__ __forceinline__ uint32_t row16_max_u32(uint32_t v) {
     return v;
 }
 
-// Unsigned max over the 64 lanes of a wave, returned as a wave-uniform value.
+// Unsigned max over the 64 lanes of a wave, returned as a wave-uniform value:
+// rows of 16, then pairs of rows (lanes 31 and 63 hold the halves' maxima), and
+// the last step on the scalar unit, which is shorter than a third cross-row move.
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
     v = row16_max_u32(v);
     v = umax(v, dpp_or_zero<kDppRowBcast15, 0xa>(v));
-    v = umax(v, dpp_or_zero<kDppRowBcast31, 0xc>(v));
-    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)v, 31);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+    return lo > hi ? lo : hi;
 }
 
 // Lowest lane for which pred holds (pred must hold in at least one lane).

@@ -261,6 +261,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         if (cloud == 0)
         for (int i = 0; i < 8; ++i) a.status[8 + i] = (int)prof_store.acc[i];
         for (int i = 0; i < 4; ++i) a.status[20 + i] = (int)prof_store.loop[i];
+        for (int i = 0; i < 4; ++i) a.status[24 + i] = (int)prof_store.sub[i];
         a.status[16] = (int)(wall_clock64() - prof_w0);       // 10 ns units
         a.status[17] = (int)((clock64() - prof_c0) >> 4);     // shader cycles / 16
 #endif
