@@ -296,6 +296,47 @@ def test_torch_operators(fb, oracle):
     assert np.array_equal(pts.cpu().numpy()[1], x[1][idx.cpu().numpy()[1]])
 
 
+@pytest.mark.parametrize("variant,b,n,m", [(WG, 6, 1500, 400), (GRID, 2, 30000, 500), (STREAM, 1, 30000, 150)])
+def test_calls_recorded_in_a_hip_graph_replay_correctly(fb, oracle, variant, b, n, m):
+    """The entry points only enqueue kernels on the caller's stream (no host
+    round trips, no memsets), so a caller may record them into a HIP graph.  The
+    graph is replayed several times with eager calls in between and every replay
+    must reproduce the oracle's result."""
+    import torch
+    x = np.stack([inputs.planes_and_clusters(n, 64000 + i) for i in range(b)])
+    xd = _dev(x)
+    ws = fb.make_workspace(b, n, m)
+    st = (m, m // 3)
+    out_e = torch.empty((b, m), dtype=torch.int32, device="cuda")
+    out_p = torch.empty((b, m), dtype=torch.int32, device="cuda")
+    out_s = torch.empty((b, sum(st)), dtype=torch.int32, device="cuda")
+    ref_e = oracle.fps_exact(x, m, 0)
+    ref_p = oracle.fps_prune(x, m, 1, 2, 3, 0)
+    ref_s = oracle.fps_stages(x, st, 1)
+    fb.ffps_exact(xd, m, 0, variant, workspace=ws, out=out_e)  # warm up outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        fb.ffps_exact(xd, m, 0, variant, workspace=ws, out=out_e)
+        fb.ffps_prune(xd, m, 1, 2, 3, 0, variant, workspace=ws, out=out_p)
+        fb.ffps_cached_stages(xd, st, 1, variant=variant, workspace=ws, out=out_s)
+    for rep in range(3):
+        print(f"replay {rep}", flush=True)
+        out_e.zero_(); out_p.zero_(); out_s.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert fb.ffps_last_status(ws) == 0
+        assert np.array_equal(out_e.cpu().numpy(), ref_e)
+        assert np.array_equal(out_p.cpu().numpy(), ref_p)
+        assert np.array_equal(out_s.cpu().numpy(), ref_s)
+        eager = fb.ffps_exact(xd, m, 3, variant, workspace=ws)  # eager work between replays
+        torch.cuda.synchronize()
+        assert np.array_equal(eager.cpu().numpy(), oracle.fps_exact(x, m, 3))
+
+
 # ------------------------------------------------- full benchmark sizes ----
 def _radius64(x, sel):
     """Coverage radius via a k-d tree in float64 (only ratios of it are used)."""
