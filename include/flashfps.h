@@ -23,6 +23,9 @@
  *   - Asynchrony: work is enqueued on `stream` (a hipStream_t passed as
  *     void*; NULL = the default stream) and the call returns without
  *     synchronising.  Outputs are valid once the stream has been synchronised.
+ *     A call only enqueues kernel launches (no host round trip, no memset, no
+ *     allocation), so it may be recorded into a HIP graph by stream capture;
+ *     the buffers and the workspace then belong to that graph's replays.
  *   - Errors: 0 on success, a negative FFPS_ERR_* code otherwise.  Arguments
  *     are validated on the host before anything is enqueued, so an invalid
  *     call has no effect on the device.
@@ -59,9 +62,9 @@ extern "C" {
 #define FFPS_VARIANT_WG 1     /* one workgroup per cloud, points resident in registers       */
 #define FFPS_VARIANT_GRID 2   /* each cloud across many CUs, points resident in registers    */
 #define FFPS_VARIANT_STREAM 3 /* one cloud across all CUs, points streamed from HBM per pass */
-/* Benchmarking knob for the multi-workgroup variants: cap on the picks accepted
- * per exchange round (1 = one pick per pass over the points; 0 = library
- * default).  The result never depends on it. */
+/* Benchmarking knob: cap on the picks accepted per round, i.e. per pass over the
+ * points (1 = one pick per pass; 0 = library default).  The result never
+ * depends on it. */
 #define FFPS_VARIANT_WITH_PICKS(variant, picks) ((variant) | ((picks) << 8))
 
 /* Library version: major * 10000 + minor * 100 + patch.  Host only. */
@@ -176,11 +179,11 @@ int ffps_gather_rows(const float *d_rows, int B, int N, int C, const int32_t *d_
 int ffps_last_status(const void *d_ws, void *stream);
 
 /*
- * Largest number of exchange rounds any cloud took in a GRID or STREAM kernel
- * of the last call on this workspace (each round delivers one or more picks),
- * or a negative status as ffps_last_status.  0 if no such kernel ran.
- * Synchronises `stream`.  Diagnostic: for a single ffps_exact launch,
- * (M - 1) / rounds = picks per cross-workgroup exchange.
+ * Largest number of rounds any cloud took in a multi-pick kernel of the last
+ * call on this workspace (each round delivers one or more picks), or a
+ * negative status as ffps_last_status.  0 if no such kernel ran (clouds of at
+ * most 256 points use a one-pick kernel).  Synchronises `stream`.  Diagnostic:
+ * for a single ffps_exact launch, (M - 1) / rounds = picks per round.
  */
 int ffps_last_rounds(const void *d_ws, void *stream);
 
