@@ -337,6 +337,33 @@ def test_calls_recorded_in_a_hip_graph_replay_correctly(fb, oracle, variant, b, 
         assert np.array_equal(eager.cpu().numpy(), oracle.fps_exact(x, m, 3))
 
 
+def test_calls_on_two_streams_with_their_own_workspaces(fb, oracle):
+    """Calls on different streams are independent when each has its own
+    workspace: two multi-workgroup runs, and a batch of small clouds beside a
+    large one, enqueued without waiting for each other."""
+    import torch
+    xa = inputs.make_config(4, N=60000)
+    xb = np.ascontiguousarray(xa[:, ::-1])
+    xs = inputs.make_config(2, B=8)
+    da, db, ds = _dev(xa), _dev(xb), _dev(xs)
+    wa, wb, wsm = fb.make_workspace(1, 60000, 700), fb.make_workspace(1, 60000, 700), fb.make_workspace(8, 1024, 300)
+    oa = torch.empty((1, 700), dtype=torch.int32, device="cuda")
+    ob = torch.empty((1, 700), dtype=torch.int32, device="cuda")
+    osm = torch.empty((8, 300), dtype=torch.int32, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for rep in range(2):
+        print(f"rep {rep}", flush=True)
+        fb.ffps_exact(da, 700, 0, GRID, workspace=wa, stream=s1, out=oa)
+        fb.ffps_exact(db, 700, 5, GRID, workspace=wb, stream=s2, out=ob)
+        fb.ffps_exact(ds, 300, 0, 0, workspace=wsm, stream=s1, out=osm)
+        torch.cuda.synchronize()
+        assert fb.ffps_last_status(wa) == 0 and fb.ffps_last_status(wb) == 0
+        assert np.array_equal(oa.cpu().numpy(), oracle.fps_exact(xa, 700, 0))
+        assert np.array_equal(ob.cpu().numpy(), oracle.fps_exact(xb, 700, 5))
+        assert np.array_equal(osm.cpu().numpy(), oracle.fps_exact(xs, 300, 0))
+
+
 # ------------------------------------------------- full benchmark sizes ----
 def _radius64(x, sel):
     """Coverage radius via a k-d tree in float64 (only ratios of it are used)."""
