@@ -1,6 +1,7 @@
-// k_fps_wg: exact FPS (Sec. 3.1, Eq. 1), one workgroup per cloud.
+// Exact FPS (Sec. 3.1, Eq. 1) with one workgroup per cloud: k_fps_wg takes one
+// pick per pass over the points, k_fps_wgm many (further down).
 //
-// The whole cloud lives in registers for the duration of the call: thread t
+// k_fps_wg: the whole cloud lives in registers for the duration of the call: thread t
 // holds points [t*P, t*P+P) and their running minimum distances, so lane order,
 // wave order and index order coincide and "lowest index wins a tie" becomes
 // "lowest lane / lowest wave wins".  Per pick: P distance updates per lane, a
@@ -133,10 +134,11 @@ static hipError_t launch_wg_t(const float *xyz, int B, int N, int M, int start, 
 // (one 16-byte LDS record); the replay wave takes the 2 * NTW reported points as
 // candidates and replays the greedy rule of Eq. 1 on them alone (fps_exchange.h)
 // for as long as the best candidate stays strictly above every lane's
-// third-best value, since no unreported point can then be the maximum.  Picks go to the
-// workers through LDS one by one while the replay is still running.  A round
-// delivers about (6 NTW^2)^(1/3) picks, so the workgroup-wide reduction of the
-// one-pick loop is paid once per ~60 picks instead of once per pick.
+// third-best value, since no unreported point can then be the maximum.  Picks
+// go to the workers through LDS one by one while the replay is still running.
+// A round delivers some tens of picks, so nothing is reduced over the whole
+// workgroup per pick: the lanes' reports need no cross-lane step at all, and
+// the replay runs inside one wave.
 struct WgmArgs {
     const float *xyz;
     int N, M, start;
