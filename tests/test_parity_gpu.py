@@ -125,6 +125,25 @@ def test_single_workgroup_picks_per_pass_do_not_change_the_result(fb, oracle):
     assert rounds[128] < rounds[7] < rounds[1]
 
 
+def test_seeded_random_sweep_of_shapes(fb, oracle):
+    """Forty seeded draws of (generator, batch, size, picks, start, kernel variant),
+    sizes log-uniform up to 40,000 points, each compared with the oracle."""
+    rng = np.random.default_rng(20260417)
+    gens = [inputs.uniform_cube, inputs.shape_cloud, inputs.planes_and_clusters,
+            lambda n, seed: inputs.make_config(4, N=n)[0] if n >= 64 else inputs.uniform_cube(n, seed)]
+    for case in range(40):
+        n = int(np.exp(rng.uniform(np.log(2), np.log(40000))))
+        b = int(rng.integers(1, 5)) if n > 3000 else int(rng.integers(1, 40))
+        m = int(rng.integers(1, min(n, 1200) + 1))
+        start = int(rng.integers(0, n))
+        variant = int(rng.choice([0, WG, GRID, STREAM])) if n <= 24576 else int(rng.choice([0, GRID, STREAM]))
+        if variant == STREAM:
+            b = min(b, 2)
+        gen = gens[int(rng.integers(0, len(gens)))]
+        x = np.stack([gen(n, 123000 + 97 * case + i) for i in range(b)])
+        _check_exact(fb, oracle, x, m, start, variant)
+
+
 @pytest.mark.parametrize("cloud", ["line", "grid2", "grid3", "dups"])
 @pytest.mark.parametrize("variant", [WG, GRID, STREAM])
 def test_ties_and_duplicates(fb, oracle, variant, cloud):
