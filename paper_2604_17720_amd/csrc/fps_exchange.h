@@ -29,21 +29,23 @@ namespace ffps {
 
 constexpr int kMaxUnits = kMaxGridWG;     // reporting units of a cloud
 constexpr int kRPL = kMaxUnits / kWave;   // unit records per lane of the gathering wave
-constexpr int kCPL = 2 * kRPL;            // candidates per lane before compaction
 constexpr int kSpinLimit = 1 << 19;
 constexpr uint32_t kNoIndex = 0x7fffffffu;  // index of a candidate that does not exist
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Exchange area: two buffers (round parity); each holds four chunk arrays
-// (A: {v_a, v_b, bound, check}, B: {x_a, y_a, z_a, check}, C: {x_b, y_b, z_b,
-// check}, D: {i_a, i_b, 0, check}) of 256 slots x 16 bytes.  Unit u uses slot
-// u, and lane L of a gathering wave reads slots L, L + 64, L + 128, L + 192: each
-// 16-byte load per lane touches one contiguous KiB, and units with consecutive
-// numbers, which hold consecutive point indices, land in different lanes.
-constexpr int kChunks = 4;
+// Exchange area: two buffers (round parity); each holds one array of 256 slots
+// x 16 bytes per chunk of a record.  A record of T candidates is, in chunks of
+// three words plus a check word,
+//   T = 2: {v0, v1, bound} {x0, y0, z0} {x1, y1, z1} {i0, i1, 0}
+//   T = 3: {v0, v1, v2} {x0, y0, z0} {x1, y1, z1} {x2, y2, z2} {i0, i1, i2} {bound, 0, 0}.
+// Unit u uses slot u, and lane L of a gathering wave reads slots L, L + 64,
+// L + 128, L + 192: each 16-byte load per lane touches one contiguous KiB, and
+// units with consecutive numbers, which hold consecutive point indices, land in
+// different lanes.
+__host__ __device__ constexpr int chunks_of(int T) { return T == 2 ? 4 : 6; }
 constexpr size_t kChunkBytes = (size_t)kMaxUnits * 16;
-constexpr size_t kBufBytes = kChunks * kChunkBytes;
+__host__ __device__ constexpr size_t buf_bytes(int T) { return chunks_of(T) * kChunkBytes; }
 
 // A chunk is valid for a round when its last word equals this value.  Memory
 // cleared to zero never validates (the round term is non-zero for round >= 1),
@@ -64,12 +66,11 @@ __device__ __forceinline__ bool chunk_ok(const u32x4 &c, uint32_t round, uint32_
 __device__ __forceinline__ void store_chunk(void *p, u32x4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
-// r*[q] = 16 bytes at p* + q * 1024, q < 4: all sixteen loads are issued before
-// the single wait, so a poll costs one round trip.
-__device__ __forceinline__ void load_chunks4(const void *pa, const void *pb, const void *pc,
-                                             const void *pd, u32x4 (&ra)[kRPL], u32x4 (&rb)[kRPL],
-                                             u32x4 (&rc)[kRPL], u32x4 (&rd)[kRPL]) {
+// r[c][q] = 16 bytes at p + c * kChunkBytes + q * 1024, q < 4: all loads are
+// issued before the single wait, so a poll costs one round trip.
+__device__ __forceinline__ void load_chunks(const char *p, u32x4 (&r)[4][kRPL]) {
     static_assert(kRPL == 4, "four slots per lane");
+    const char *pa = p, *pb = p + kChunkBytes, *pc = p + 2 * kChunkBytes, *pd = p + 3 * kChunkBytes;
     asm volatile(
         "global_load_dwordx4 %0, %16, off sc1\n\t"
         "global_load_dwordx4 %1, %16, off offset:1024 sc1\n\t"
@@ -88,10 +89,49 @@ __device__ __forceinline__ void load_chunks4(const void *pa, const void *pb, con
         "global_load_dwordx4 %14, %19, off offset:2048 sc1\n\t"
         "global_load_dwordx4 %15, %19, off offset:3072 sc1\n\t"
         "s_waitcnt vmcnt(0)"
-        : "=&v"(ra[0]), "=&v"(ra[1]), "=&v"(ra[2]), "=&v"(ra[3]), "=&v"(rb[0]), "=&v"(rb[1]),
-          "=&v"(rb[2]), "=&v"(rb[3]), "=&v"(rc[0]), "=&v"(rc[1]), "=&v"(rc[2]), "=&v"(rc[3]),
-          "=&v"(rd[0]), "=&v"(rd[1]), "=&v"(rd[2]), "=&v"(rd[3])
+        : "=&v"(r[0][0]), "=&v"(r[0][1]), "=&v"(r[0][2]), "=&v"(r[0][3]), "=&v"(r[1][0]),
+          "=&v"(r[1][1]), "=&v"(r[1][2]), "=&v"(r[1][3]), "=&v"(r[2][0]), "=&v"(r[2][1]),
+          "=&v"(r[2][2]), "=&v"(r[2][3]), "=&v"(r[3][0]), "=&v"(r[3][1]), "=&v"(r[3][2]),
+          "=&v"(r[3][3])
         : "v"(pa), "v"(pb), "v"(pc), "v"(pd)
+        : "memory");
+}
+__device__ __forceinline__ void load_chunks(const char *p, u32x4 (&r)[6][kRPL]) {
+    static_assert(kRPL == 4, "four slots per lane");
+    const char *pa = p, *pb = p + kChunkBytes, *pc = p + 2 * kChunkBytes, *pd = p + 3 * kChunkBytes,
+               *pe = p + 4 * kChunkBytes, *pf = p + 5 * kChunkBytes;
+    asm volatile(
+        "global_load_dwordx4 %0, %24, off sc1\n\t"
+        "global_load_dwordx4 %1, %24, off offset:1024 sc1\n\t"
+        "global_load_dwordx4 %2, %24, off offset:2048 sc1\n\t"
+        "global_load_dwordx4 %3, %24, off offset:3072 sc1\n\t"
+        "global_load_dwordx4 %4, %25, off sc1\n\t"
+        "global_load_dwordx4 %5, %25, off offset:1024 sc1\n\t"
+        "global_load_dwordx4 %6, %25, off offset:2048 sc1\n\t"
+        "global_load_dwordx4 %7, %25, off offset:3072 sc1\n\t"
+        "global_load_dwordx4 %8, %26, off sc1\n\t"
+        "global_load_dwordx4 %9, %26, off offset:1024 sc1\n\t"
+        "global_load_dwordx4 %10, %26, off offset:2048 sc1\n\t"
+        "global_load_dwordx4 %11, %26, off offset:3072 sc1\n\t"
+        "global_load_dwordx4 %12, %27, off sc1\n\t"
+        "global_load_dwordx4 %13, %27, off offset:1024 sc1\n\t"
+        "global_load_dwordx4 %14, %27, off offset:2048 sc1\n\t"
+        "global_load_dwordx4 %15, %27, off offset:3072 sc1\n\t"
+        "global_load_dwordx4 %16, %28, off sc1\n\t"
+        "global_load_dwordx4 %17, %28, off offset:1024 sc1\n\t"
+        "global_load_dwordx4 %18, %28, off offset:2048 sc1\n\t"
+        "global_load_dwordx4 %19, %28, off offset:3072 sc1\n\t"
+        "global_load_dwordx4 %20, %29, off sc1\n\t"
+        "global_load_dwordx4 %21, %29, off offset:1024 sc1\n\t"
+        "global_load_dwordx4 %22, %29, off offset:2048 sc1\n\t"
+        "global_load_dwordx4 %23, %29, off offset:3072 sc1\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(r[0][0]), "=&v"(r[0][1]), "=&v"(r[0][2]), "=&v"(r[0][3]), "=&v"(r[1][0]),
+          "=&v"(r[1][1]), "=&v"(r[1][2]), "=&v"(r[1][3]), "=&v"(r[2][0]), "=&v"(r[2][1]),
+          "=&v"(r[2][2]), "=&v"(r[2][3]), "=&v"(r[3][0]), "=&v"(r[3][1]), "=&v"(r[3][2]),
+          "=&v"(r[3][3]), "=&v"(r[4][0]), "=&v"(r[4][1]), "=&v"(r[4][2]), "=&v"(r[4][3]),
+          "=&v"(r[5][0]), "=&v"(r[5][1]), "=&v"(r[5][2]), "=&v"(r[5][3])
+        : "v"(pa), "v"(pb), "v"(pc), "v"(pd), "v"(pe), "v"(pf)
         : "memory");
 }
 
@@ -144,43 +184,54 @@ __device__ __forceinline__ int best_lane(uint32_t v, uint32_t i, uint32_t vmax, 
     return first_lane(v == vmax && i == imin);
 }
 
-// Two best (value, index) pairs and the third value of a set, in (value
-// descending, index ascending) order.
-struct Top3 {
-    uint32_t v1, v2, v3;
-    uint32_t i1, i2;
+// The K best (value, index) pairs of a set and the value that follows them,
+// in (value descending, index ascending) order.
+template <int K>
+struct TopK {
+    uint32_t v[K + 1];
+    uint32_t i[K];
 };
 
-// Merge the Top3 of the participating lanes (`act`) into one.  l1, l2 receive
-// the lanes that supplied the first and second entry, s2 whether the second
-// entry was lane l2's second (l1 == l2) rather than its first.  MAXF / MINF
-// reduce over the participating lanes and return wave-uniform values.
-template <typename MAXF, typename MINF>
-__device__ __forceinline__ Top3 merge_top3(const Top3 &t, bool act, int lane, MAXF maxf, MINF minf,
-                                           int &l1, int &l2, bool &s2) {
-    Top3 r;
-    const uint32_t a1 = act ? t.v1 : 0u, a2 = act ? t.v2 : 0u, a3 = act ? t.v3 : 0u;
-    const uint32_t i1 = act ? t.i1 : 0xffffffffu, i2 = act ? t.i2 : 0xffffffffu;
-    r.v1 = maxf(a1);
-    l1 = best_lane(a1, i1, r.v1, minf);
-    r.i1 = (uint32_t)readlane_i((int)i1, l1);
-    const uint32_t b = lane == l1 ? a2 : a1, bi = lane == l1 ? i2 : i1;
-    r.v2 = maxf(b);
-    l2 = best_lane(b, bi, r.v2, minf);
-    r.i2 = (uint32_t)readlane_i((int)bi, l2);
-    s2 = l1 == l2;
-    const uint32_t c = lane == l1 ? (s2 ? a3 : a2) : (lane == l2 ? a2 : a1);
-    r.v3 = maxf(c);
+// Merge the TopK of the participating lanes (`act`) into one.  src[r] receives
+// the lane that supplied entry r and ent[r] which of that lane's entries it
+// was.  MAXF / MINF reduce over the participating lanes and return wave-uniform
+// values.
+template <int K, typename MAXF, typename MINF>
+__device__ __forceinline__ TopK<K> merge_topk(const TopK<K> &t, bool act, int lane, MAXF maxf,
+                                              MINF minf, int (&src)[K], int (&ent)[K]) {
+    TopK<K> r;
+    int cur = 0;  // entries of this lane already taken
+    uint32_t hv = act ? t.v[0] : 0u, hi = act ? t.i[0] : 0xffffffffu;  // this lane's next entry
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        r.v[k] = maxf(hv);
+        const int l = best_lane(hv, hi, r.v[k], minf);
+        r.i[k] = (uint32_t)readlane_i((int)hi, l);
+        src[k] = l;
+        ent[k] = readlane_i(cur, l);
+        if (lane == l) {
+            ++cur;
+            hv = t.v[K];
+            hi = 0xffffffffu;
+#pragma unroll
+            for (int e = 1; e < K; ++e) {
+                hv = cur == e ? t.v[e] : hv;
+                hi = cur == e ? t.i[e] : hi;
+            }
+        }
+    }
+    r.v[K] = maxf(hv);
     return r;
 }
 
-// What a workgroup contributes to a round: its two best points (any order)
+// What a reporting unit contributes to a round: its T best points (any order)
 // with their current values and indices, and the bound on its other points.
 // A candidate that does not exist has value 0 and index kNoIndex.
+template <int T>
 struct RoundInput {
-    uint32_t va, vb, bound;
-    float xa, ya, za, xb, yb, zb;
-    uint32_t ia, ib;
+    uint32_t v[T], bound;
+    float x[T], y[T], z[T];
+    uint32_t i[T];
 };
 
 // LDS used by the wave that runs exchange_round.
@@ -325,6 +376,9 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
     // compared.
     const bool packed = total >= 1 && total <= 2 * kWave && V - T < (1u << 24);
     FFPS_SUB(1);
+#ifdef FFPS_EXP_STATS
+    if (prof) { prof->sub[3] += (uint32_t)total; if (T != Bound) prof->acc[7] += 1; }
+#endif
 #ifdef FFPS_PROFILE
     if (prof && packed) prof->acc[total <= kWave ? 5 : 6] += 1;
 #endif
@@ -486,41 +540,47 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
 // the replay is still running); the wave with `writer` set records the picks in
 // idx_out / md_out.  Returns the number of picks of the round (1 .. cap), or -1
 // after setting *status when another unit's record never arrived.
+template <int T>
 __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int U, int unit0, int nsub,
                                               bool writer, int lane, uint32_t round,
-                                              const RoundInput &in, int npicked, int cap,
+                                              const RoundInput<T> &in, int npicked, int cap,
                                               int32_t *idx_out, float *md_out, int *status,
                                               RoundProf *prof) {
+    static_assert(T == 2 || T == 3, "two or three candidates per unit");
+    constexpr int NCH = chunks_of(T);
+    constexpr int KC = T * kRPL;  // candidates per lane before compaction
     // ---- publish ----
-    char *buf = exchange + (size_t)(round & 1) * kBufBytes;
+    char *buf = exchange + (size_t)(round & 1) * buf_bytes(T);
     if (lane < nsub) {
-        u32x4 c0, c1, c2, c3;
-        c0.x = in.va; c0.y = in.vb; c0.z = in.bound;
-        c0.w = chunk_check(c0.x, c0.y, c0.z, round, 0);
-        c1.x = f2u(in.xa); c1.y = f2u(in.ya); c1.z = f2u(in.za);
-        c1.w = chunk_check(c1.x, c1.y, c1.z, round, 1);
-        c2.x = f2u(in.xb); c2.y = f2u(in.yb); c2.z = f2u(in.zb);
-        c2.w = chunk_check(c2.x, c2.y, c2.z, round, 2);
-        c3.x = in.ia; c3.y = in.ib; c3.z = 0u;
-        c3.w = chunk_check(c3.x, c3.y, c3.z, round, 3);
+        uint32_t d[NCH][3] = {};
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            d[0][t] = in.v[t];
+            d[1 + t][0] = f2u(in.x[t]); d[1 + t][1] = f2u(in.y[t]); d[1 + t][2] = f2u(in.z[t]);
+            d[T + 1][t] = in.i[t];
+        }
+        if (T == 2) d[0][2] = in.bound; else d[NCH - 1][0] = in.bound;
         const size_t so = (size_t)(unit0 + lane) * 16;
-        store_chunk(buf + so, c0);
-        store_chunk(buf + kChunkBytes + so, c1);
-        store_chunk(buf + 2 * kChunkBytes + so, c2);
-        store_chunk(buf + 3 * kChunkBytes + so, c3);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            u32x4 ch;
+            ch.x = d[c][0]; ch.y = d[c][1]; ch.z = d[c][2];
+            ch.w = chunk_check(ch.x, ch.y, ch.z, round, (uint32_t)c);
+            store_chunk(buf + c * kChunkBytes + so, ch);
+        }
     }
     FFPS_STAMP(prof, 2);
     // ---- gather: lane L reads slots (= units) q*64+L ----
-    u32x4 ra[kRPL], rb[kRPL], rc[kRPL], rd[kRPL];
+    u32x4 r[NCH][kRPL];
     bool gave_up = false;
     for (int spin = 0;; ++spin) {
-        const char *p = buf + (size_t)lane * 16;
-        load_chunks4(p, p + kChunkBytes, p + 2 * kChunkBytes, p + 3 * kChunkBytes, ra, rb, rc, rd);
+        load_chunks(buf + (size_t)lane * 16, r);
         bool all = true;
 #pragma unroll
         for (int q = 0; q < kRPL; ++q) {
-            bool ok = chunk_ok(ra[q], round, 0) && chunk_ok(rb[q], round, 1) &&
-                      chunk_ok(rc[q], round, 2) && chunk_ok(rd[q], round, 3);
+            bool ok = true;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) ok = ok && chunk_ok(r[c][q], round, (uint32_t)c);
             all = all && (ok || q * kWave + lane >= U);
         }
 #ifdef FFPS_PROFILE
@@ -537,21 +597,26 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int U
         if (lane == 0) __hip_atomic_store(status, -5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return -1;
     }
-    // candidate c = 2q + r of this lane: unit q*64 + lane, its r-th entry
-    uint32_t cv[kCPL], ci[kCPL], lb = 0u;
-    float cx[kCPL], cy[kCPL], cz[kCPL];
+    // candidate c = T q + t of this lane: unit q*64 + lane, its t-th entry
+    uint32_t cv[KC], ci[KC], lb = 0u;
+    float cx[KC], cy[KC], cz[KC];
 #pragma unroll
     for (int q = 0; q < kRPL; ++q) {
         const bool present = q * kWave + lane < U;  // absent records: value 0, bound 0
-        cv[2 * q] = present ? ra[q].x : 0u;
-        cv[2 * q + 1] = present ? ra[q].y : 0u;
-        lb = umax(lb, present ? ra[q].z : 0u);
-        ci[2 * q] = present ? rd[q].x : kNoIndex;
-        ci[2 * q + 1] = present ? rd[q].y : kNoIndex;
-        cx[2 * q] = u2f(rb[q].x); cy[2 * q] = u2f(rb[q].y); cz[2 * q] = u2f(rb[q].z);
-        cx[2 * q + 1] = u2f(rc[q].x); cy[2 * q + 1] = u2f(rc[q].y); cz[2 * q + 1] = u2f(rc[q].z);
+        const uint32_t vals[3] = {r[0][q].x, r[0][q].y, r[0][q].z};
+        const uint32_t idxs[3] = {r[T + 1][q].x, r[T + 1][q].y, r[T + 1][q].z};
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            cv[T * q + t] = present ? vals[t] : 0u;
+            ci[T * q + t] = present ? idxs[t] : kNoIndex;
+            cx[T * q + t] = u2f(r[1 + t][q].x);
+            cy[T * q + t] = u2f(r[1 + t][q].y);
+            cz[T * q + t] = u2f(r[1 + t][q].z);
+        }
+        const uint32_t bnd = T == 2 ? r[0][q].z : r[NCH - 1][q].x;
+        lb = umax(lb, present ? bnd : 0u);
     }
-    const int cnt = replay_round<kCPL>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
+    const int cnt = replay_round<KC>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
     // one workgroup records the picks (the same wave wrote pk_idx / pk_val)
     if (writer) {
         for (int c = lane; c < cnt; c += kWave) {

@@ -28,10 +28,14 @@ namespace ffps {
 
 namespace {
 
-struct WaveTop {  // a worker wave's two best points and the bound on its others
-    Top3 t;
-    float x1, y1, z1, x2, y2, z2;
-    uint32_t pad;
+// Candidates a reporting unit contributes to a round.  Three were tried: more
+// picks per round, but a dearer round (larger records, a fourth reduction per
+// merge, half as many candidates again to count and compact) and slower overall.
+constexpr int kT = 2;
+
+struct WaveTop {  // a worker wave's kT best points and the bound on its others
+    TopK<kT> t;
+    float x[kT], y[kT], z[kT];
 };
 
 struct GridArgs {  // pointers are those of the first cloud of the launch
@@ -44,7 +48,7 @@ struct GridArgs {  // pointers are those of the first cloud of the launch
     long idx_stride;   // elements between the outputs of consecutive clouds
     float *md_out;
     long md_stride;
-    char *exchange;    // per cloud: two buffers of kBufBytes
+    char *exchange;    // per cloud: two buffers of buf_bytes(kT)
     int *status;
     int max_picks;
 };
@@ -71,7 +75,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
     a.xyz += (size_t)cloud * a.N * 3;
     a.idx_out += cloud * a.idx_stride;
     if (a.md_out) a.md_out += cloud * a.md_stride;
-    a.exchange += (size_t)cloud * 2 * kBufBytes;
+    a.exchange += (size_t)cloud * 2 * buf_bytes(kT);
     if (a.start_dev) a.start = a.start_dev[cloud];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -153,37 +157,52 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
                 }
             }
             if (s_abort || applied >= a.M) break;
-            // ---- 1b. per-lane top three values (element numbers for the first two) ----
-            float a1 = m[0], a2 = 0.f, a3 = 0.f;
-            int j1 = 0, j2 = 0;
+            // ---- 1b. the lane's kT + 1 largest values (element numbers for the first kT) ----
+            float top[kT + 1];
+            int tj[kT];
+            top[0] = m[0];
+#pragma unroll
+            for (int r = 1; r <= kT; ++r) top[r] = 0.f;
+#pragma unroll
+            for (int r = 0; r < kT; ++r) tj[r] = 0;
 #pragma unroll
             for (int j = 1; j < P; ++j) {
-                float v = m[j];
-                bool g1 = v > a1, g2 = v > a2;  // strict: the earlier (lower) j keeps a tie
-                a3 = fmaxf(a3, fminf(v, a2));
-                j2 = g1 ? j1 : (g2 ? j : j2);
-                a2 = fmaxf(a2, fminf(v, a1));
-                j1 = g1 ? j : j1;
-                a1 = fmaxf(a1, v);
+                const float v = m[j];
+                bool g[kT + 1];  // strict: the earlier (lower) j keeps a tie
+#pragma unroll
+                for (int r = 0; r <= kT; ++r) g[r] = v > top[r];
+#pragma unroll
+                for (int r = kT; r >= 1; --r) {
+                    top[r] = fmaxf(top[r], fminf(v, top[r - 1]));
+                    if (r < kT) tj[r] = g[r - 1] ? tj[r - 1] : (g[r] ? j : tj[r]);
+                }
+                tj[0] = g[0] ? j : tj[0];
+                top[0] = fmaxf(top[0], v);
             }
-            // ---- 1c. wave top two + bound (equal values: lowest index first) ----
-            Top3 mine;
-            mine.v1 = f2u(a1); mine.v2 = f2u(a2); mine.v3 = f2u(a3);
-            mine.i1 = index_of(j1); mine.i2 = index_of(j2);
-            int l1, l2;
-            bool s2;
-            const Top3 wt = merge_top3(mine, true, lane, [](uint32_t v) { return wave_max_u32(v); },
-                                       [](uint32_t v) { return wave_min_u32(v); }, l1, l2, s2);
-            const int e1 = readlane_i(j1, l1);
-            const int e2 = readlane_i(s2 ? j2 : j1, l2);
-            float x1, y1, z1, x2, y2, z2;
-            pick_xyz<P>(x, y, z, e1, l1, x1, y1, z1);
-            pick_xyz<P>(x, y, z, e2, l2, x2, y2, z2);
+            // ---- 1c. the wave's kT best + bound (equal values: lowest index first) ----
+            TopK<kT> mine;
+#pragma unroll
+            for (int r = 0; r <= kT; ++r) mine.v[r] = f2u(top[r]);
+#pragma unroll
+            for (int r = 0; r < kT; ++r) mine.i[r] = index_of(tj[r]);
+            int src[kT], ent[kT];
+            const TopK<kT> wt = merge_topk<kT>(mine, true, lane, [](uint32_t v) { return wave_max_u32(v); },
+                                               [](uint32_t v) { return wave_min_u32(v); }, src, ent);
+            float wx[kT], wy[kT], wz[kT];
+#pragma unroll
+            for (int r = 0; r < kT; ++r) {
+                int ej = tj[0];  // element number of this lane's ent[r]-th entry
+#pragma unroll
+                for (int e = 1; e < kT; ++e) ej = ent[r] == e ? tj[e] : ej;
+                pick_xyz<P>(x, y, z, readlane_i(ej, src[r]), src[r], wx[r], wy[r], wz[r]);
+            }
             if (lane == 0) {
                 WaveTop &o = wtop[wk];
                 o.t = wt;
-                o.x1 = x1; o.y1 = y1; o.z1 = z1;
-                o.x2 = x2; o.y2 = y2; o.z2 = z2;
+#pragma unroll
+                for (int r = 0; r < kT; ++r) {
+                    o.x[r] = wx[r]; o.y[r] = wy[r]; o.z[r] = wz[r];
+                }
             }
             __syncthreads();  // wave tops ready for the communication wave
         }
@@ -205,37 +224,44 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         FFPS_STAMP(prof, 0);
         __syncthreads();  // workers have applied every pick so far and filled wtop
         FFPS_STAMP(prof, 1);
-        RoundInput in;
+        RoundInput<kT> in;
         int cnt;
         const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
         if (a.wave_units) {
             // ---- 2a. every worker wave is a unit of its own: lane s reports wave s ----
             const WaveTop &o = wtop[lane < NWK ? lane : 0];
-            in.va = o.t.v1; in.vb = o.t.v2; in.bound = o.t.v3;
-            in.ia = o.t.i1; in.ib = o.t.i2;
-            in.xa = o.x1; in.ya = o.y1; in.za = o.z1;
-            in.xb = o.x2; in.yb = o.y2; in.zb = o.z2;
+#pragma unroll
+            for (int r = 0; r < kT; ++r) {
+                in.v[r] = o.t.v[r]; in.i[r] = o.t.i[r];
+                in.x[r] = o.x[r]; in.y[r] = o.y[r]; in.z[r] = o.z[r];
+            }
+            in.bound = o.t.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
-            cnt = exchange_round(L, a.exchange, G * NWK, w * NWK, NWK, w == 0, lane, round, in,
-                                 npicked, cap, a.idx_out, a.md_out, a.status, prof);
+            cnt = exchange_round<kT>(L, a.exchange, G * NWK, w * NWK, NWK, w == 0, lane, round, in,
+                                     npicked, cap, a.idx_out, a.md_out, a.status, prof);
         } else {
-            // ---- 2a. workgroup top two + bound from the worker waves' triples ----
+            // ---- 2a. the workgroup's kT best + bound from the worker waves' ----
             const bool act = lane < NWK;
-            int w1, w2;
-            bool s2w;
-            const Top3 g3 = merge_top3(wtop[act ? lane : 0].t, act, lane,
-                                       [](uint32_t v) { return row_max_uniform(v); },
-                                       [](uint32_t v) { return row_min_uniform(v); }, w1, w2, s2w);
-            // candidate a = wave w1's first; candidate b = wave w2's first, or w1's second
-            in.va = g3.v1; in.vb = g3.v2; in.bound = g3.v3;
-            in.ia = g3.i1; in.ib = g3.i2;
-            in.xa = wtop[w1].x1; in.ya = wtop[w1].y1; in.za = wtop[w1].z1;
-            in.xb = s2w ? wtop[w1].x2 : wtop[w2].x1;
-            in.yb = s2w ? wtop[w1].y2 : wtop[w2].y1;
-            in.zb = s2w ? wtop[w1].z2 : wtop[w2].z1;
+            int src[kT], ent[kT];
+            const TopK<kT> g3 = merge_topk<kT>(wtop[act ? lane : 0].t, act, lane,
+                                               [](uint32_t v) { return row_max_uniform(v); },
+                                               [](uint32_t v) { return row_min_uniform(v); }, src, ent);
+#pragma unroll
+            for (int r = 0; r < kT; ++r) {
+                in.v[r] = g3.v[r]; in.i[r] = g3.i[r];
+                const WaveTop &o = wtop[src[r]];  // entry r is wave src[r]'s ent[r]-th
+                in.x[r] = o.x[0]; in.y[r] = o.y[0]; in.z[r] = o.z[0];
+#pragma unroll
+                for (int e = 1; e < kT; ++e) {
+                    in.x[r] = ent[r] == e ? o.x[e] : in.x[r];
+                    in.y[r] = ent[r] == e ? o.y[e] : in.y[r];
+                    in.z[r] = ent[r] == e ? o.z[e] : in.z[r];
+                }
+            }
+            in.bound = g3.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
-            cnt = exchange_round(L, a.exchange, G, w, 1, w == 0, lane, round, in, npicked, cap,
-                                 a.idx_out, a.md_out, a.status, prof);
+            cnt = exchange_round<kT>(L, a.exchange, G, w, 1, w == 0, lane, round, in, npicked, cap,
+                                     a.idx_out, a.md_out, a.status, prof);
         }
         if (cnt < 0) {
             if (lane == 0) {
@@ -301,7 +327,7 @@ int units_of(int N, int g) {
 
 }  // namespace
 
-size_t grid_exchange_bytes_per_cloud() { return 2 * kBufBytes; }
+size_t grid_exchange_bytes_per_cloud() { return 2 * buf_bytes(kT); }  // the streaming kernel reports two as well
 
 long grid_capacity(int num_cu) {
     int G = num_cu < kMaxGridWG ? num_cu : kMaxGridWG;

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
     if (a.start_dev) a.start = a.start_dev[0];
     constexpr int NT = kStreamThreads, NW = NT / kWave;
     __shared__ RoundLds L;
-    __shared__ Top3 wtop[NW];
+    __shared__ TopK<2> wtop[NW];
     __shared__ int s_cnt, s_abort;
 
     const int G = gridDim.x;
@@ -152,39 +152,36 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
             if (two) finish(B, g2);
         }
         // ---- 1b. wave top two + bound (value ties broken on the index) ----
-        Top3 mine;
-        mine.v1 = f2u(fmaxf(t1, 0.f)); mine.v2 = f2u(fmaxf(t2, 0.f)); mine.v3 = f2u(fmaxf(t3, 0.f));
-        mine.i1 = j1; mine.i2 = j2;
-        int l1, l2;
-        bool s2;
-        const Top3 wt = merge_top3(mine, true, lane, [](uint32_t v) { return wave_max_u32(v); },
-                                   [](uint32_t v) { return wave_min_u32(v); }, l1, l2, s2);
+        TopK<2> mine;
+        mine.v[0] = f2u(fmaxf(t1, 0.f)); mine.v[1] = f2u(fmaxf(t2, 0.f)); mine.v[2] = f2u(fmaxf(t3, 0.f));
+        mine.i[0] = j1; mine.i[1] = j2;
+        int src[2], ent[2];
+        const TopK<2> wt = merge_topk<2>(mine, true, lane, [](uint32_t v) { return wave_max_u32(v); },
+                                         [](uint32_t v) { return wave_min_u32(v); }, src, ent);
         if (lane == 0) wtop[wave] = wt;
         __syncthreads();  // wave tops visible; every wave is done with the picks in L.pk
 
         if (wave == 0) {
             // ---- 2a. workgroup top two + bound ----
             const bool act = lane < NW;
-            int w1, w2;
-            bool s2w;
-            const Top3 g3 = merge_top3(wtop[act ? lane : 0], act, lane,
-                                       [](uint32_t v) { return row_max_uniform(v); },
-                                       [](uint32_t v) { return row_min_uniform(v); }, w1, w2, s2w);
+            const TopK<2> g3 = merge_topk<2>(wtop[act ? lane : 0], act, lane,
+                                             [](uint32_t v) { return row_max_uniform(v); },
+                                             [](uint32_t v) { return row_min_uniform(v); }, src, ent);
             // an index that does not exist (slice of one point) has value 0
-            RoundInput in;
-            in.va = g3.v1; in.vb = g3.v2; in.bound = g3.v3;
-            const uint32_t ia = g3.i1, ib = g3.i2;
-            const bool ea = ia < (uint32_t)a.N, eb = ib < (uint32_t)a.N;
-            in.ia = ea ? ia : kNoIndex;
-            in.ib = eb ? ib : kNoIndex;
-            in.xa = ea ? a.xyz[3 * (size_t)(ea ? ia : 0) + 0] : 0.f;
-            in.ya = ea ? a.xyz[3 * (size_t)(ea ? ia : 0) + 1] : 0.f;
-            in.za = ea ? a.xyz[3 * (size_t)(ea ? ia : 0) + 2] : 0.f;
-            in.xb = eb ? a.xyz[3 * (size_t)(eb ? ib : 0) + 0] : 0.f;
-            in.yb = eb ? a.xyz[3 * (size_t)(eb ? ib : 0) + 1] : 0.f;
-            in.zb = eb ? a.xyz[3 * (size_t)(eb ? ib : 0) + 2] : 0.f;
+            RoundInput<2> in;
+            in.bound = g3.v[2];
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const uint32_t ir = g3.i[r];
+                const bool e = ir < (uint32_t)a.N;
+                in.v[r] = g3.v[r];
+                in.i[r] = e ? ir : kNoIndex;
+                in.x[r] = e ? a.xyz[3 * (size_t)(e ? ir : 0) + 0] : 0.f;
+                in.y[r] = e ? a.xyz[3 * (size_t)(e ? ir : 0) + 1] : 0.f;
+                in.z[r] = e ? a.xyz[3 * (size_t)(e ? ir : 0) + 2] : 0.f;
+            }
             const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
-            const int cnt = exchange_round(L, a.exchange, G, w, 1, w == 0, lane, round, in, npicked, cap,
+            const int cnt = exchange_round<2>(L, a.exchange, G, w, 1, w == 0, lane, round, in, npicked, cap,
                                            a.idx_out, a.md_out, a.status, nullptr);
             if (lane == 0) {
                 s_cnt = cnt < 0 ? 0 : cnt;
