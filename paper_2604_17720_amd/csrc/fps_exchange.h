@@ -376,9 +376,6 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
     // compared.
     const bool packed = total >= 1 && total <= 2 * kWave && V - T < (1u << 24);
     FFPS_SUB(1);
-#ifdef FFPS_EXP_STATS
-    if (prof) { prof->sub[3] += (uint32_t)total; if (T != Bound) prof->acc[7] += 1; }
-#endif
 #ifdef FFPS_PROFILE
     if (prof && packed) prof->acc[total <= kWave ? 5 : 6] += 1;
 #endif
