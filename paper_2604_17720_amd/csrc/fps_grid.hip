@@ -335,11 +335,7 @@ long grid_capacity(int num_cu) {
 }
 
 GridPlan plan_fps_grid(int B, int N, int num_cu) {
-#ifdef FFPS_EXP_MAXG
-    const int maxG = FFPS_EXP_MAXG;
-#else
     const int maxG = num_cu < kMaxGridWG ? num_cu : kMaxGridWG;
-#endif
     // at least 128 points per workgroup before another CU is worth a record ...
     int want = (N + 127) / 128;
     if (want > maxG) want = maxG;
