@@ -5,8 +5,9 @@
 // belongs to workgroup i mod G) and its running minimum distance in registers
 // for the whole call.  The strided assignment spreads any run of consecutive
 // indices over all workgroups, so an input that is already in farthest-point
-// order (a layer of a stage chain) yields as many picks per round as any other.  A workgroup
-// is one COMMUNICATION wave (wave 0) plus NWK WORKER waves that own the points.
+// order (a layer of a stage chain) yields as many picks per round as any other.
+// A workgroup is one COMMUNICATION wave (wave 0) plus NWK WORKER waves that own
+// the points.
 // Waves i and i+4 of a workgroup share a SIMD, so waves 4, 8 and 12 exit at
 // once: the communication wave, whose dependent chain sets the pace, then has
 // its SIMD to itself and the workers fill the other three.
@@ -15,9 +16,11 @@
 // picks.  The workers apply the picks of a round to their points one by one,
 // taking them from LDS while the communication wave is still producing them,
 // then reduce their slice to its two best points and an upper bound on every
-// other point (the third-best value); the communication wave merges the worker
-// waves' results and runs the next round.  The picks are exactly those of the
-// one-pick-per-pass loop.
+// other point (the third-best value).  The communication wave merges the worker
+// waves' results into the workgroup's report, or, when workgroups x worker waves
+// fit the exchange area, passes every wave's result on as a report of its own
+// (more reporting units, more picks per round), and runs the next round.  The
+// picks are exactly those of the one-pick-per-pass loop.
 //
 // Exit: every wait is bounded or ends when the communication wave says so; a
 // workgroup that gives up sets the status word and leaves, and the others then
