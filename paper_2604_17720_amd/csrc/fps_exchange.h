@@ -407,6 +407,26 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
             lds_write16(pk_off + c * 16, s);
             L.pk_key[c] = K;
         };
+        // The wave-wide max of the next keys with the hand-over of pick c written
+        // between its steps: a DPP step must wait two issue slots for the result of
+        // the one before, and the hand-over's independent moves and writes fill them.
+        auto max_and_hand_over = [&](uint32_t key, int c, uint32_t Kc) {
+            uint32_t v = key;
+            u32x4 s;
+            v = umax(v, dpp_or_zero<kDppRowShr1>(v));
+            s.x = f2u(px); s.y = f2u(py);
+            v = umax(v, dpp_or_zero<kDppRowShr2>(v));
+            s.z = f2u(pz); s.w = (uint32_t)(npicked + c);
+            v = umax(v, dpp_or_zero<kDppRowShr4>(v));
+            const uint32_t at = pk_off + c * 16;
+            v = umax(v, dpp_or_zero<kDppRowShr8>(v));
+            lds_write16(at, s);
+            v = umax(v, dpp_or_zero<kDppRowBcast15, 0xa>(v));
+            L.pk_key[c] = Kc;
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)v, 31);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+            return lo > hi ? lo : hi;
+        };
         if (total <= kWave) {
             // one candidate per lane: lane L takes position L, code = L
             const bool h = lane < total;
@@ -419,11 +439,11 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
 #ifdef FFPS_PROFILE
             const uint64_t lc0 = clock64();
 #endif
+            // the first pick of the round is never below the threshold
+            uint32_t d = __builtin_elementwise_sub_sat(v0, T);
+            uint32_t key = (d << 7) | (uint32_t)lane;
+            uint32_t K = wave_max_u32(key);
             while (true) {
-                const uint32_t d = __builtin_elementwise_sub_sat(v0, T);
-                const uint32_t key = (d << 7) | (uint32_t)lane;
-                uint32_t K = wave_max_u32(key);
-                if ((K >> 7) == 0) break;  // cannot happen for the first pick
                 pl = (int)(K & 127u);
                 if (__builtin_expect(__builtin_amdgcn_ballot_w64(((key ^ K) - 1u) < 127u) != 0, 0)) {
                     // several candidates share the best value: the lowest index wins
@@ -434,9 +454,16 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
                 px = readlane_f(x0, pl);
                 py = readlane_f(y0, pl);
                 pz = readlane_f(z0, pl);
-                hand_over(cnt, K);
-                if (++cnt >= cap) break;
+                const int c = cnt++;
+                if (cnt >= cap) {
+                    hand_over(c, K);
+                    break;
+                }
                 v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
+                d = __builtin_elementwise_sub_sat(v0, T);
+                key = (d << 7) | (uint32_t)lane;
+                K = max_and_hand_over(key, c, K);
+                if ((K >> 7) == 0) break;
             }
 #ifdef FFPS_PROFILE
             if (prof) {
@@ -469,15 +496,20 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
 #ifdef FFPS_PROFILE
             const uint64_t lc0 = clock64();
 #endif
-            while (true) {
+            uint32_t bd, key;
+            float bx, by, bz;
+            bool sec;
+            auto keys_of_lane = [&]() {
                 const uint32_t d0 = __builtin_elementwise_sub_sat(v0, T);
                 const uint32_t d1 = __builtin_elementwise_sub_sat(v1, T);
-                const bool sec = d1 > d0;  // strict: equal values put the lower index forward
-                const float bx = sec ? x1 : x0, by = sec ? y1 : y0, bz = sec ? z1 : z0;
-                const uint32_t bd = sec ? d1 : d0;
-                const uint32_t key = (bd << 7) | ((uint32_t)lane << 1) | (sec ? 1u : 0u);
-                uint32_t K = wave_max_u32(key);
-                if ((K >> 7) == 0) break;
+                sec = d1 > d0;  // strict: equal values put the lower index forward
+                bx = sec ? x1 : x0; by = sec ? y1 : y0; bz = sec ? z1 : z0;
+                bd = sec ? d1 : d0;
+                key = (bd << 7) | ((uint32_t)lane << 1) | (sec ? 1u : 0u);
+            };
+            keys_of_lane();
+            uint32_t K = wave_max_u32(key);  // the first pick is never below the threshold
+            while (true) {
                 pl = (int)((K >> 1) & 63u);
                 if (__builtin_expect(__builtin_amdgcn_ballot_w64(((key ^ K) - 1u) < 127u) != 0, 0)) {
                     const uint32_t bidx = sec ? i1 : i0;
@@ -488,10 +520,16 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
                 px = readlane_f(bx, pl);
                 py = readlane_f(by, pl);
                 pz = readlane_f(bz, pl);
-                hand_over(cnt, K);
-                if (++cnt >= cap) break;
+                const int c = cnt++;
+                if (cnt >= cap) {
+                    hand_over(c, K);
+                    break;
+                }
                 v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
                 v1 = f2u(fminf(u2f(v1), sqdist(x1, y1, z1, px, py, pz)));
+                keys_of_lane();
+                K = max_and_hand_over(key, c, K);
+                if ((K >> 7) == 0) break;
             }
 #ifdef FFPS_PROFILE
             if (prof) {
