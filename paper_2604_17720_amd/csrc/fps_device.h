@@ -26,6 +26,15 @@ __device__ __forceinline__ float sqdist(float x, float y, float z, float lx, flo
     return __fadd_rn(__fadd_rn(xx, yy), zz);
 }
 
+// min of two distances as one instruction.  fminf would first canonicalise its
+// operands (an extra instruction per call) to quiet signalling NaNs, which
+// cannot occur here: distances of finite points are never NaN.
+__device__ __forceinline__ float min_dist(float a, float b) {
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // Distances are >= +0 (or +inf), so their IEEE bit patterns order like
 // unsigned integers; reductions run on the bits.
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }

@@ -459,7 +459,7 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
                     hand_over(c, K);
                     break;
                 }
-                v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
+                v0 = f2u(min_dist(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
                 d = __builtin_elementwise_sub_sat(v0, T);
                 key = (d << 7) | (uint32_t)lane;
                 K = max_and_hand_over(key, c, K);
@@ -525,8 +525,8 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
                     hand_over(c, K);
                     break;
                 }
-                v0 = f2u(fminf(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
-                v1 = f2u(fminf(u2f(v1), sqdist(x1, y1, z1, px, py, pz)));
+                v0 = f2u(min_dist(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
+                v1 = f2u(min_dist(u2f(v1), sqdist(x1, y1, z1, px, py, pz)));
                 keys_of_lane();
                 K = max_and_hand_over(key, c, K);
                 if ((K >> 7) == 0) break;
