@@ -273,10 +273,22 @@ struct RoundProf {
 // bounds on all points that are not candidates.  Pick number c of the round is
 // written as {x, y, z, npicked + c} to L.pk[c] (16-byte LDS writes, in pick
 // order, so other waves may consume them while the replay is still running),
-// its index and value to L.pk_idx[c] / L.pk_val[c].  Returns the number of
-// picks (1 .. cap).  The candidate arrays are used up.
+// and what record_picks needs to name its index and value is left in L.
+// Returns the number of picks (1 .. cap) and how they were noted.  The
+// candidate arrays are used up.
+struct RoundResult {
+    int cnt;        // picks of the round, or -1 when the round failed
+    bool by_key;    // picks noted as keys (L.pk_key, L.tab_idx) rather than in L.pk_idx / L.pk_val
+    uint32_t T;     // threshold the keys are relative to
+};
+
+// Writes index (and value) of the picks of a round to the outputs; run by the
+// wave that ran the round, in one workgroup of the cloud.
+__device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const RoundResult &r,
+                                             int npicked, int32_t *idx_out, float *md_out);
+
 template <int KC>
-__device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv)[KC],
+__device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint32_t (&cv)[KC],
                                             uint32_t (&ci)[KC], float (&cx)[KC], float (&cy)[KC],
                                             float (&cz)[KC], uint32_t lb, int npicked, int cap,
                                             RoundProf *prof) {
@@ -538,12 +550,6 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
             }
 #endif
         }
-        // index and value of every pick from its noted key
-        for (int c = lane; c < cnt; c += kWave) {
-            const uint32_t K = L.pk_key[c];
-            L.pk_idx[c] = L.tab_idx[K & 127u];
-            L.pk_val[c] = (K >> 7) + T;
-        }
     } else {
         // a single pick (best candidate not above the bound, or cap 1), or values
         // spread too far above the threshold for the packed key: work on all
@@ -564,7 +570,29 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
                 cv[q] = f2u(fminf(u2f(cv[q]), sqdist(cx[q], cy[q], cz[q], px, py, pz)));
         }
     }
-    return cnt;
+    RoundResult res;
+    res.cnt = cnt;
+    res.by_key = packed;
+    res.T = T;
+    return res;
+}
+
+__device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const RoundResult &r,
+                                             int npicked, int32_t *idx_out, float *md_out) {
+    for (int c = lane; c < r.cnt; c += kWave) {
+        uint32_t idx, val;
+        if (r.by_key) {
+            // the key holds the pick's value above the threshold and the code of its candidate
+            const uint32_t K = L.pk_key[c];
+            idx = L.tab_idx[K & 127u];
+            val = (K >> 7) + r.T;
+        } else {
+            idx = L.pk_idx[c];
+            val = L.pk_val[c];
+        }
+        idx_out[npicked + c] = (int32_t)idx;
+        if (md_out) md_out[npicked + c] = u2f(val);
+    }
 }
 
 // One round, run by ONE full wave of a workgroup.  The cloud has U reporting
@@ -572,15 +600,14 @@ __device__ __forceinline__ int replay_round(RoundLds &L, int lane, uint32_t (&cv
 // this wave publish `in` as unit unit0 + lane.  The wave then gathers all U
 // records, replays, writes each pick as {x, y, z, npicked + c} to L.pk[c]
 // (16-byte LDS writes, in pick order, so other waves may consume them while
-// the replay is still running); the wave with `writer` set records the picks in
-// idx_out / md_out.  Returns the number of picks of the round (1 .. cap), or -1
-// after setting *status when another unit's record never arrived.
+// the replay is still running).  Returns the picks of the round (1 .. cap; see
+// record_picks), or a count of -1 after setting *status when another unit's
+// record never arrived.
 template <int T>
-__device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int U, int unit0, int nsub,
-                                              bool writer, int lane, uint32_t round,
-                                              const RoundInput<T> &in, int npicked, int cap,
-                                              int32_t *idx_out, float *md_out, int *status,
-                                              RoundProf *prof) {
+__device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchange, int U, int unit0,
+                                                      int nsub, int lane, uint32_t round,
+                                                      const RoundInput<T> &in, int npicked, int cap,
+                                                      int *status, RoundProf *prof) {
     static_assert(T == 2 || T == 3, "two or three candidates per unit");
     constexpr int NCH = chunks_of(T);
     constexpr int KC = T * kRPL;  // candidates per lane before compaction
@@ -630,7 +657,11 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int U
     FFPS_STAMP(prof, 3);
     if (gave_up) {
         if (lane == 0) __hip_atomic_store(status, -5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return -1;
+        RoundResult failed;
+        failed.cnt = -1;
+        failed.by_key = false;
+        failed.T = 0u;
+        return failed;
     }
     // candidate c = T q + t of this lane: unit q*64 + lane, its t-th entry
     uint32_t cv[KC], ci[KC], lb = 0u;
@@ -651,15 +682,7 @@ __device__ __forceinline__ int exchange_round(RoundLds &L, char *exchange, int U
         const uint32_t bnd = T == 2 ? r[0][q].z : r[NCH - 1][q].x;
         lb = umax(lb, present ? bnd : 0u);
     }
-    const int cnt = replay_round<KC>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
-    // one workgroup records the picks (the same wave wrote pk_idx / pk_val)
-    if (writer) {
-        for (int c = lane; c < cnt; c += kWave) {
-            idx_out[npicked + c] = (int32_t)L.pk_idx[c];
-            if (md_out) md_out[npicked + c] = u2f(L.pk_val[c]);
-        }
-    }
-    return cnt;
+    return replay_round<KC>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
 }
 
 }  // namespace ffps

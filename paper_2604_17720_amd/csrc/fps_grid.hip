@@ -228,7 +228,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         __syncthreads();  // workers have applied every pick so far and filled wtop
         FFPS_STAMP(prof, 1);
         RoundInput<kT> in;
-        int cnt;
+        RoundResult res;
         const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
         if (a.wave_units) {
             // ---- 2a. every worker wave is a unit of its own: lane s reports wave s ----
@@ -240,8 +240,8 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             }
             in.bound = o.t.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
-            cnt = exchange_round<kT>(L, a.exchange, G * NWK, w * NWK, NWK, w == 0, lane, round, in,
-                                     npicked, cap, a.idx_out, a.md_out, a.status, prof);
+            res = exchange_round<kT>(L, a.exchange, G * NWK, w * NWK, NWK, lane, round, in, npicked,
+                                     cap, a.status, prof);
         } else {
             // ---- 2a. the workgroup's kT best + bound from the worker waves' ----
             const bool act = lane < NWK;
@@ -263,9 +263,10 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             }
             in.bound = g3.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
-            cnt = exchange_round<kT>(L, a.exchange, G, w, 1, w == 0, lane, round, in, npicked, cap,
-                                     a.idx_out, a.md_out, a.status, prof);
+            res = exchange_round<kT>(L, a.exchange, G, w, 1, lane, round, in, npicked, cap, a.status,
+                                     prof);
         }
+        const int cnt = res.cnt;
         if (cnt < 0) {
             if (lane == 0) {
                 s_abort = 1;
@@ -275,12 +276,14 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             }
             return;
         }
-        npicked += cnt;
+        // release the workers first, then note the picks (workgroup 0 only)
         if (lane == 0) {
             u32x2 f;
-            f.x = round; f.y = (uint32_t)npicked;
+            f.x = round; f.y = (uint32_t)(npicked + cnt);
             lds_write8(fin_off, f);
         }
+        if (w == 0) record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
+        npicked += cnt;
         FFPS_STAMP(prof, 4);
     }
     if (w == 0 && lane == 0) {

@@ -181,12 +181,13 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
                 in.z[r] = e ? a.xyz[3 * (size_t)(e ? ir : 0) + 2] : 0.f;
             }
             const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
-            const int cnt = exchange_round<2>(L, a.exchange, G, w, 1, w == 0, lane, round, in, npicked, cap,
-                                           a.idx_out, a.md_out, a.status, nullptr);
+            const RoundResult res = exchange_round<2>(L, a.exchange, G, w, 1, lane, round, in, npicked,
+                                                      cap, a.status, nullptr);
             if (lane == 0) {
-                s_cnt = cnt < 0 ? 0 : cnt;
-                if (cnt < 0) s_abort = 1;
+                s_cnt = res.cnt < 0 ? 0 : res.cnt;
+                if (res.cnt < 0) s_abort = 1;
             }
+            if (w == 0 && res.cnt > 0) record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
         }
         __syncthreads();  // picks of this round visible to all waves
         if (s_abort) return;

@@ -303,17 +303,15 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
         }
         const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
         FFPS_STAMP(prof, 2);
-        const int cnt = replay_round<KC>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
-        for (int c = lane; c < cnt; c += kWave) {
-            a.idx_out[npicked + c] = (int32_t)L.pk_idx[c];
-            if (a.md_out) a.md_out[npicked + c] = u2f(L.pk_val[c]);
-        }
-        npicked += cnt;
+        const RoundResult res = replay_round<KC>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
+        // release the workers first, then note the picks
         if (lane == 0) {
             u32x2 f;
-            f.x = (uint32_t)round; f.y = (uint32_t)npicked;
+            f.x = (uint32_t)round; f.y = (uint32_t)(npicked + res.cnt);
             lds_write8(fin_off, f);
         }
+        record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
+        npicked += res.cnt;
         FFPS_STAMP(prof, 4);
     }
     if (lane == 0) {
