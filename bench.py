@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes one launch of the dominant kernel really moves, from the hardware
 # counters in profiles/k_fps_grid_config4_hbm_counters.md (FETCH_SIZE x 2.000 +
 # WRITE_SIZE x 1.000, calibrated on a 256 MiB copy): exchange records only.
-MEASURED_TRAFFIC_BYTES = 2.000 * 190514.84 * 1024 + 1.000 * 25891.38 * 1024
+MEASURED_TRAFFIC_BYTES = 2.000 * 186856.25 * 1024 + 1.000 * 25891.39 * 1024
 
 
 def updates_of_chain(sizes):
