@@ -92,8 +92,11 @@ def test_grid_clusters_of_workgroups_per_cloud(fb, oracle, b, n, m):
     _check_exact(fb, oracle, x, min(m, 64), n - 1, 0)
 
 
-@pytest.mark.parametrize("n,m", [(30000, 500), (70001, 900), (262144, 64), (300001, 300)])
+@pytest.mark.parametrize("n,m", [(30000, 500), (70001, 900), (262144, 64), (300001, 300),
+                                 (1000003, 120), (2500000, 48)])
 def test_grid_multi_point_per_lane(fb, oracle, n, m):
+    """Up to sixteen points per worker lane; the two largest clouds run on the
+    twelve-worker-wave shapes."""
     x = inputs.make_config(4, N=n)[0]
     _check_exact(fb, oracle, x, m, 17, GRID)
 
