@@ -188,6 +188,22 @@ int ffps_last_status(const void *d_ws, void *stream);
 int ffps_last_rounds(const void *d_ws, void *stream);
 
 /*
+ * How a call on B clouds of N points would be laid over a device with num_cu
+ * compute units (256 on MI355X), without touching any device.  Host only.
+ *   *kernel              FFPS_VARIANT_WG / _GRID / _STREAM that `variant`
+ *                        (AUTO or explicit) resolves to
+ *   *wg_per_cloud        workgroups that share one cloud (1 for WG)
+ *   *units_per_cloud     reporting units of a round (0 for the one-pick kernel
+ *                        that serves clouds of at most 256 points, and clouds
+ *                        beyond 4608 points when WG is forced)
+ *   *clouds_per_launch   clouds one kernel launch carries
+ * Any output pointer may be NULL.  FFPS_ERR_INVALID_ARG for B, N, num_cu < 1,
+ * FFPS_ERR_UNSUPPORTED_SIZE when the requested variant cannot hold N.
+ */
+int ffps_describe_plan(int B, int N, int variant, int num_cu, int *kernel, int *wg_per_cloud,
+                       int *units_per_cloud, int *clouds_per_launch);
+
+/*
  * Reference measurement for the multi-workgroup kernels: runs `iters`
  * (1 .. 2^20) plain grid barriers (one device-scope atomic arrive plus a spin
  * on the counter each) over one workgroup per CU, the launch shape of the GRID

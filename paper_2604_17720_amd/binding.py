@@ -37,7 +37,7 @@ def variant_with_picks(variant: int, picks: int) -> int:
 
 EXPORTS = ["ffps_version", "ffps_strerror", "ffps_prune_sizes", "ffps_workspace_bytes",
            "ffps_exact", "ffps_prune", "ffps_cached_stages", "ffps_last_status",
-           "ffps_last_rounds", "ffps_barrier_probe", "ffps_gather_rows"]
+           "ffps_last_rounds", "ffps_barrier_probe", "ffps_gather_rows", "ffps_describe_plan"]
 
 
 class FlashFPSError(RuntimeError):
@@ -74,6 +74,7 @@ def lib() -> ctypes.CDLL:
         L.ffps_last_rounds.argtypes = [c_vp, c_vp]
         L.ffps_gather_rows.argtypes = [c_vp, c_int, c_int, c_int, c_vp, ctypes.c_long, c_int, c_vp, c_vp]
         L.ffps_barrier_probe.argtypes = [c_int, c_vp, c_sz, c_vp, ctypes.POINTER(ctypes.c_float)]
+        L.ffps_describe_plan.argtypes = [c_int, c_int, c_int, c_int, ip, ip, ip, ip]
         for n in EXPORTS:
             if n not in ("ffps_strerror",):
                 getattr(L, n).restype = c_int
@@ -97,6 +98,17 @@ def ffps_prune_sizes(N, M, keep_num, keep_den, flags):
     if rc:
         raise FlashFPSError(rc, "ffps_prune_sizes")
     return nc.value, k.value, r.value
+
+
+def ffps_describe_plan(B, N, variant=FFPS_VARIANT_AUTO, num_cu=256):
+    """(kernel, workgroups per cloud, reporting units per cloud, clouds per launch)
+    a call on B clouds of N points would use on a device with num_cu CUs."""
+    k, g, u, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    rc = lib().ffps_describe_plan(B, N, variant, num_cu, ctypes.byref(k), ctypes.byref(g),
+                                  ctypes.byref(u), ctypes.byref(c))
+    if rc:
+        raise FlashFPSError(rc, "ffps_describe_plan")
+    return k.value, g.value, u.value, c.value
 
 
 def ffps_workspace_bytes(B, N, M) -> int:

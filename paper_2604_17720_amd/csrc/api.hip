@@ -314,6 +314,32 @@ int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_sta
     return FFPS_OK;
 }
 
+int ffps_describe_plan(int B, int N, int variant, int num_cu, int *kernel, int *wg_per_cloud,
+                       int *units_per_cloud, int *clouds_per_launch) {
+    if (B < 1 || N < 1 || num_cu < 1 || check_variant(variant)) return FFPS_ERR_INVALID_ARG;
+    Device dev{FFPS_OK, num_cu};
+    const int v = resolve_variant(B, N, variant, dev);
+    if (v < 0) return v;
+    int wg = 1, units = 0, clouds = B;
+    if (v == FFPS_VARIANT_WG) {
+        units = wg_units(N);
+    } else if (v == FFPS_VARIANT_GRID) {
+        const GridPlan plan = plan_fps_grid(B, N, num_cu);
+        wg = plan.wg_per_cloud;
+        units = plan.units_per_cloud;
+        clouds = plan.clouds_per_launch;
+    } else {
+        wg = stream_workgroups(N, num_cu);
+        units = wg;
+        clouds = 1;
+    }
+    if (kernel) *kernel = v;
+    if (wg_per_cloud) *wg_per_cloud = wg;
+    if (units_per_cloud) *units_per_cloud = units;
+    if (clouds_per_launch) *clouds_per_launch = clouds;
+    return FFPS_OK;
+}
+
 int ffps_last_status(const void *d_ws, void *stream) {
     if (!d_ws) return FFPS_ERR_INVALID_ARG;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;

@@ -363,6 +363,7 @@ GridPlan plan_fps_grid(int B, int N, int num_cu) {
         }
     }
     GridPlan p;
+    p.units_per_cloud = best_units;
     p.wg_per_cloud = best;
     p.clouds_per_launch = maxG / best < 1 ? 1 : maxG / best;
     if (p.clouds_per_launch > B) p.clouds_per_launch = B;

@@ -14,6 +14,8 @@ constexpr int kMaxPicksPerRound = FFPS_MAX_PICKS;  // picks one round may delive
 // ---- fps_wg.hip: one workgroup per cloud ------------------------------------
 int wg_capacity();   // largest N the single-workgroup kernels hold
 int wgm_capacity();  // largest N of the multi-pick single-workgroup kernel
+int wg_units(int N);  // reporting units of the kernel that serves N points (0: one-pick kernel)
+int stream_workgroups(int N, int num_cu);  // workgroups the streaming kernel spreads N points over
 // In all FPS launchers `start_dev`, when not null, is a device array with one
 // start index per cloud that overrides `start` (read by the kernel).
 // `max_picks` caps the picks one pass over the points may deliver (0: no cap
@@ -32,6 +34,7 @@ long grid_capacity(int num_cu);          // largest N the register-resident grid
 struct GridPlan {
     int wg_per_cloud;
     int clouds_per_launch;
+    int units_per_cloud;  // reporting units of a round
 };
 GridPlan plan_fps_grid(int B, int N, int num_cu);
 // `clouds` clouds (densely packed, outputs idx_stride / md_stride apart) in one

@@ -199,14 +199,18 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
 
 }  // namespace
 
-hipError_t launch_fps_stream(const float *xyz, float *mind, int N, int M, int start,
-                             const int *start_dev, int32_t *idx, float *md, void *exchange,
-                             int *status, int num_cu, int max_picks, hipStream_t s) {
+int stream_workgroups(int N, int num_cu) {
     int maxG = num_cu < kMaxGridWG ? num_cu : kMaxGridWG;
     // a workgroup pass covers 4096 points per step; do not spread thinner than that
     int G = (N + 4095) / 4096;
     if (G > maxG) G = maxG;
-    if (G < 1) G = 1;
+    return G < 1 ? 1 : G;
+}
+
+hipError_t launch_fps_stream(const float *xyz, float *mind, int N, int M, int start,
+                             const int *start_dev, int32_t *idx, float *md, void *exchange,
+                             int *status, int num_cu, int max_picks, hipStream_t s) {
+    const int G = stream_workgroups(N, num_cu);
     StreamArgs a;
     a.xyz = xyz; a.mind = mind; a.N = N; a.M = M; a.start = start; a.start_dev = start_dev;
     a.chunk = ((N + G - 1) / G + 3) / 4 * 4;

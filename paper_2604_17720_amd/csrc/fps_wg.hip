@@ -338,6 +338,11 @@ int wg_capacity() { return 1024 * 24; }
 
 int wgm_capacity() { return 6 * kWave * 12; }
 
+int wg_units(int N) {
+    if (N <= 64 * 4 || N > wgm_capacity()) return 0;
+    return N <= 3 * kWave * 6 ? 3 * kWave : 6 * kWave;  // one reporting unit per worker lane
+}
+
 // Very small clouds (one wave holds them) and clouds beyond the multi-pick
 // kernel's capacity use the one-pick kernel, the others the multi-pick kernel.
 // Shapes are ordered by capacity; the first one that holds N is used.

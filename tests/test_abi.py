@@ -108,6 +108,46 @@ def test_entry_points_validate_before_touching_the_device():
     assert stages([50], L_=0) == fb.FFPS_ERR_INVALID_ARG
 
 
+def test_plan_of_the_five_configurations_and_its_limits():
+    """Host logic behind FFPS_VARIANT_AUTO on a 256-CU device: which kernel runs,
+    on how many workgroups, with how many reporting units per round."""
+    import paper_2604_17720_amd.binding as fb
+    WG, GRID, STREAM = fb.FFPS_VARIANT_WG, fb.FFPS_VARIANT_GRID, fb.FFPS_VARIANT_STREAM
+    plan = fb.ffps_describe_plan
+    assert plan(1, 1024) == (WG, 1, 192, 1)            # config 1: one unit per worker lane
+    assert plan(32, 1024) == (WG, 1, 192, 32)          # config 2
+    assert plan(8, 16384) == (GRID, 32, 192, 8)        # config 3: 32 workgroups x 6 reporting waves
+    assert plan(1, 200000) == (GRID, 256, 256, 1)      # config 4: one unit per workgroup
+    assert plan(1, 300000) == (GRID, 256, 256, 1)      # config 5
+    # the boundaries of the kernels
+    assert plan(1, 256)[0] == WG and plan(1, 256)[2] == 0          # one-pick kernel, no rounds
+    assert plan(1, 257)[2] == 192 and plan(1, 1152)[2] == 192 and plan(1, 1153)[2] == 384
+    assert plan(1, 4608)[0] == WG and plan(1, 4609)[0] == GRID
+    assert plan(1, 256 * 12288)[0] == GRID and plan(1, 256 * 12288 + 1)[0] == STREAM
+    assert plan(1, 1 << 25) == (STREAM, 256, 256, 1)
+    # explicit variants and their size limits
+    assert plan(4, 20000, WG) == (WG, 1, 0, 4)
+    with pytest.raises(fb.FlashFPSError) as e:
+        plan(1, 24577, WG)
+    assert e.value.code == fb.FFPS_ERR_UNSUPPORTED_SIZE
+    with pytest.raises(fb.FlashFPSError):
+        plan(1, 256 * 12288 + 1, GRID)
+    for bad in ((0, 10, 0, 256), (1, 0, 0, 256), (1, 10, 7, 256), (1, 10, 0, 0)):
+        with pytest.raises(fb.FlashFPSError) as e:
+            plan(*bad)
+        assert e.value.code == fb.FFPS_ERR_INVALID_ARG
+    # invariants of the cluster plan over a sweep of shapes
+    for B in (1, 2, 3, 8, 17, 40, 300):
+        for N in (4609, 9000, 12500, 16384, 50000, 100000, 786433, 3000000):
+            k, g, u, c = plan(B, N, GRID)
+            assert k == GRID and 1 <= g <= 256 and 1 <= c <= B and g * c <= 256
+            assert g <= u <= 256 and u % g == 0 and u // g in (1, 3, 6, 12)
+            assert N <= g * 12288                      # every workgroup's slice fits its registers
+    # a smaller device gets fewer workgroups, never more units than the exchange area holds
+    k, g, u, c = plan(1, 200000, GRID, 64)
+    assert g <= 64 and u <= 256
+
+
 def test_torch_operators_register_and_infer_shapes():
     """torch.ops.flashfps.* exist and their shape functions work on fake tensors
     (no kernel runs, so no GPU is needed)."""
