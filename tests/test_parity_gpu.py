@@ -105,11 +105,12 @@ def test_grid_multi_point_per_lane(fb, oracle, n, m):
     (3, 256, 256), (3, 257, 257), (2, 384, 200), (2, 385, 385), (5, 768, 300), (2, 769, 500),
     (33, 1152, 200), (2, 1153, 700), (2, 1536, 900), (2, 1537, 300), (2, 2304, 1200),
     (2, 2305, 400), (2, 3072, 700), (2, 3073, 300), (2, 4608, 2500), (2, 4609, 300),
-    (2, 8192, 300), (2, 8193, 200),
+    (2, 8192, 300), (2, 8193, 200), (600, 1024, 40), (300, 4608, 60),
 ])
 def test_single_workgroup_kernel_shapes(fb, oracle, b, n, m):
     """Every shape of the one-workgroup-per-cloud kernels, at its capacity and one
-    point past it (which selects the next shape), on surface-like clouds."""
+    point past it (which selects the next shape), on surface-like clouds; the
+    last two batches hold more clouds than the device has CUs."""
     x = np.stack([inputs.shape_cloud(n, 52000 + 7 * n + i) for i in range(b)])
     _check_exact(fb, oracle, x, m, n // 3, WG)
 
