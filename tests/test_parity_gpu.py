@@ -129,6 +129,19 @@ def test_single_workgroup_picks_per_pass_do_not_change_the_result(fb, oracle):
     assert rounds[128] < rounds[7] < rounds[1]
 
 
+@pytest.mark.parametrize("variant", [WG, GRID, STREAM])
+@pytest.mark.parametrize("scale", [3e-20, 2e18])
+def test_subnormal_and_huge_distances(fb, oracle, variant, scale):
+    """Clouds scaled so that squared distances are subnormal fp32 numbers (they
+    must be kept, not flushed to zero: R11) or close to the largest finite one."""
+    for n, m in ((700, 300), (6000, 400)):
+        x = (inputs.shape_cloud(n, 4400 + n).astype(np.float64) * scale).astype(np.float32)
+        if scale < 1:
+            d = oracle.fps_exact(x, m, 0, return_maxdist=True)[1][1:]
+            assert (d < np.finfo(np.float32).tiny).any() and (d > 0).all()  # really subnormal
+        _check_exact(fb, oracle, x, m, 0, variant)
+
+
 def test_seeded_random_sweep_of_shapes(fb, oracle):
     """Forty seeded draws of (generator, batch, size, picks, start, kernel variant),
     sizes log-uniform up to 40,000 points, each compared with the oracle."""
