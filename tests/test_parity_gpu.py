@@ -142,6 +142,17 @@ def test_subnormal_and_huge_distances(fb, oracle, variant, scale):
         _check_exact(fb, oracle, x, m, 0, variant)
 
 
+@pytest.mark.parametrize("variant", [WG, GRID, STREAM])
+def test_all_points_identical(fb, oracle, variant):
+    """Every distance is zero: after the start index, index 0 is returned over
+    and over (the argmax runs over all points, the lowest index wins)."""
+    for n, m, start in ((200, 40, 7), (3000, 60, 2999), (20000, 30, 5)):
+        x = np.tile(np.array([[0.25, -1.5, 3.0]], dtype=np.float32), (n, 1))
+        ref = oracle.fps_exact(x, m, start)
+        assert ref[0] == start and (ref[1:] == 0).all()
+        _check_exact(fb, oracle, x, m, start, variant)
+
+
 def test_seeded_random_sweep_of_shapes(fb, oracle):
     """Forty seeded draws of (generator, batch, size, picks, start, kernel variant),
     sizes log-uniform up to 40,000 points, each compared with the oracle."""
