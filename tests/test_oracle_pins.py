@@ -144,6 +144,13 @@ def test_invariants(oracle):
     assert np.array_equal(a, b)
     # M == N returns a permutation
     assert sorted(oracle.fps_exact(g, 60, 7).tolist()) == list(range(60))
+    # identical points: every distance is 0, the argmax over all points returns index 0
+    same = np.tile(np.float32([[0.25, -1.5, 3.0]]), (40, 1))
+    i2, d2 = oracle.fps_exact(same, 9, 7, return_maxdist=True)
+    assert i2.tolist() == [7] + [0] * 8 and np.all(d2[1:] == 0)
+    # scaling by a power of two is exact: same picks, distances scaled by its square
+    i3, d3 = oracle.fps_exact(x * np.float32(2.0 ** -40), 700, 5, return_maxdist=True)
+    assert np.array_equal(i3, idx) and np.array_equal(d3[1:], md[1:] * np.float32(2.0 ** -80))
 
 
 def test_batched_equals_per_cloud(oracle):
