@@ -18,8 +18,9 @@
  *     tie goes to the lowest index.  With these rules the result is unique,
  *     independent of the launch shape, and identical from run to run.
  *   - Ownership: the caller owns every buffer.  The library allocates no
- *     device memory and keeps no mutable global state; calls on different
- *     streams are independent provided they use different workspaces.
+ *     device memory and keeps no state besides a per-device note of facts that
+ *     never change (device kind, CU count); calls on different streams are
+ *     independent provided they use different workspaces.
  *   - Asynchrony: work is enqueued on `stream` (a hipStream_t passed as
  *     void*; NULL = the default stream) and the call returns without
  *     synchronising.  Outputs are valid once the stream has been synchronised.
@@ -118,7 +119,7 @@ int ffps_exact(const float *d_xyz, int B, int N, int M, int start_idx, int varia
  *               the ascending list of the N-k indices the FPS part did not pick
  *               (drawn from the full cloud, not from the candidates).
  * keep = 1/1 (p = 0) gives exactly ffps_exact.  k_out_host (may be NULL)
- * receives k.  Other arguments as ffps_exact.
+ * receives k.  Other arguments as ffps_exact; B <= 65535.
  *
  * With FFPS_FLAG_PERM the two deterministic strided rules are replaced by the
  * literal random draws of Alg. 1, made reproducible by `seed` (cloud b uses
@@ -150,6 +151,7 @@ int ffps_prune(const float *d_xyz, int B, int N, int M, int start_idx, int keep_
  *   d_idx        out [B][S], S = sum of M_stages; layer l of cloud b starts at
  *                d_idx[b*S + M_stages[0] + ... + M_stages[l-1]]
  *   d_ws         workspace of ws_bytes >= ffps_workspace_bytes(B, N, M_stages[0])
+ * B <= 65535.
  */
 int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_stages,
                        int start_idx, int keep_num, int keep_den, unsigned flags, uint64_t seed,

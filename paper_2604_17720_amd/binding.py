@@ -138,10 +138,23 @@ def _prep(xyz):
     return torch, xyz, int(xyz.shape[0]), int(xyz.shape[1])
 
 
-def make_workspace(B, N, M, device="cuda"):
-    """Device workspace (uint8 tensor) large enough for any call with these sizes."""
+def make_workspace(B, N, M, device="cuda", stream=None):
+    """Device workspace (uint8 tensor) large enough for any call with these sizes.
+    With `stream` it is allocated as that stream's memory, so the caching
+    allocator does not hand it to other work before the stream has finished."""
     torch = _torch()
-    return torch.empty(ffps_workspace_bytes(B, N, M), dtype=torch.uint8, device=device)
+    n = ffps_workspace_bytes(B, N, M)
+    if stream is None:
+        return torch.empty(n, dtype=torch.uint8, device=device)
+    with torch.cuda.stream(stream):
+        return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def _empty(torch, shape, dtype, device, stream):
+    if stream is None:
+        return torch.empty(shape, dtype=dtype, device=device)
+    with torch.cuda.stream(stream):
+        return torch.empty(shape, dtype=dtype, device=device)
 
 
 def _stream(torch, stream):
@@ -156,9 +169,9 @@ def ffps_exact(xyz, M, start_idx=0, variant=FFPS_VARIANT_AUTO, return_maxdist=Fa
     torch, x, B, N = _prep(xyz)
     if not (1 <= M <= N):
         raise FlashFPSError(FFPS_ERR_INVALID_ARG, "ffps_exact")
-    ws = make_workspace(B, N, M, x.device) if workspace is None else workspace
-    idx = torch.empty((B, M), dtype=torch.int32, device=x.device) if out is None else out
-    md = torch.empty((B, M), dtype=torch.float32, device=x.device) if return_maxdist else None
+    ws = make_workspace(B, N, M, x.device, stream) if workspace is None else workspace
+    idx = _empty(torch, (B, M), torch.int32, x.device, stream) if out is None else out
+    md = _empty(torch, (B, M), torch.float32, x.device, stream) if return_maxdist else None
     rc = lib().ffps_exact(x.data_ptr(), B, N, M, start_idx, variant, idx.data_ptr(),
                           md.data_ptr() if md is not None else None, ws.data_ptr(), ws.numel(),
                           _stream(torch, stream))
@@ -173,8 +186,8 @@ def ffps_prune(xyz, M, keep_num, keep_den, flags=FFPS_FLAG_CP | FFPS_FLAG_IP, st
     torch, x, B, N = _prep(xyz)
     if not (1 <= M <= N):
         raise FlashFPSError(FFPS_ERR_INVALID_ARG, "ffps_prune")
-    ws = make_workspace(B, N, M, x.device) if workspace is None else workspace
-    idx = torch.empty((B, M), dtype=torch.int32, device=x.device) if out is None else out
+    ws = make_workspace(B, N, M, x.device, stream) if workspace is None else workspace
+    idx = _empty(torch, (B, M), torch.int32, x.device, stream) if out is None else out
     k = ctypes.c_int()
     rc = lib().ffps_prune(x.data_ptr(), B, N, M, start_idx, keep_num, keep_den, flags, seed, variant,
                           idx.data_ptr(), ctypes.byref(k), ws.data_ptr(), ws.numel(),
@@ -193,9 +206,9 @@ def ffps_cached_stages(xyz, M_stages, mode=FFPS_MODE_CACHED, keep_num=1, keep_de
     ms = [int(m) for m in M_stages]
     if not ms or not (1 <= ms[0] <= N):
         raise FlashFPSError(FFPS_ERR_INVALID_ARG, "ffps_cached_stages")
-    ws = make_workspace(B, N, ms[0], x.device) if workspace is None else workspace
+    ws = make_workspace(B, N, ms[0], x.device, stream) if workspace is None else workspace
     S = sum(ms)
-    idx = torch.empty((B, S), dtype=torch.int32, device=x.device) if out is None else out
+    idx = _empty(torch, (B, S), torch.int32, x.device, stream) if out is None else out
     arr = (ctypes.c_int * len(ms))(*ms)
     rc = lib().ffps_cached_stages(x.data_ptr(), B, N, len(ms), arr, start_idx, keep_num, keep_den,
                                   flags, seed, mode, variant, idx.data_ptr(), ws.data_ptr(), ws.numel(),
@@ -222,7 +235,7 @@ def ffps_last_rounds(workspace, stream=None) -> int:
 def ffps_barrier_probe(iters, workspace=None, stream=None) -> float:
     """Mean time of one plain grid barrier (microseconds) in the GRID launch shape."""
     torch = _torch()
-    ws = make_workspace(1, 1, 1) if workspace is None else workspace
+    ws = make_workspace(1, 1, 1, stream=stream) if workspace is None else workspace
     out = ctypes.c_float()
     rc = lib().ffps_barrier_probe(iters, ws.data_ptr(), ws.numel(), _stream(torch, stream),
                                   ctypes.byref(out))
@@ -244,7 +257,7 @@ def ffps_gather_rows(rows, idx, stream=None):
     if int(idx.shape[0]) != B:
         raise ValueError("batch sizes differ")
     stride = int(idx.stride(0)) if B > 1 else max(int(idx.stride(0)), S)
-    out = torch.empty((B, S, C), dtype=torch.float32, device=rows.device)
+    out = _empty(torch, (B, S, C), torch.float32, rows.device, stream)
     rc = lib().ffps_gather_rows(rows.data_ptr(), B, N, C, idx.data_ptr(), stride, S, out.data_ptr(),
                                 _stream(torch, stream))
     if rc:

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/flashfps.h"
 #include "fps_launch.h"
 
@@ -38,12 +40,16 @@ struct Device {
     int num_cu;
 };
 
-// Properties of the current device (queried per call: cheap, and keeps the
-// library free of mutable global state).
-Device query_device() {
+// Facts about a device that never change while the process lives (is it a
+// gfx950, how many CUs), looked up once per device: the full property query is
+// far dearer than a small launch.  This cache is the library's only state.
+constexpr int kMaxDevices = 64;
+std::mutex g_device_mutex;
+bool g_device_known[kMaxDevices];
+Device g_device[kMaxDevices];
+
+Device query_device_uncached(int dev) {
     Device d{FFPS_ERR_LAUNCH_FAILED, 0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return d;
     hipDeviceProp_t p;
     if (hipGetDeviceProperties(&p, dev) != hipSuccess) return d;
     if (strncmp(p.gcnArchName, "gfx950", 6) != 0) {
@@ -55,15 +61,34 @@ Device query_device() {
     return d;
 }
 
+// Properties of the current device.
+Device query_device(int *dev_out = nullptr) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return Device{FFPS_ERR_LAUNCH_FAILED, 0};
+    if (dev_out) *dev_out = dev;
+    if (dev < 0 || dev >= kMaxDevices) return query_device_uncached(dev);
+    std::lock_guard<std::mutex> lock(g_device_mutex);
+    if (!g_device_known[dev]) {
+        g_device[dev] = query_device_uncached(dev);
+        // a failed query is tried again by the next call
+        g_device_known[dev] = g_device[dev].ok != FFPS_ERR_LAUNCH_FAILED;
+    }
+    return g_device[dev];
+}
+
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? FFPS_OK : FFPS_ERR_LAUNCH_FAILED; }
 
-int check_common(const void *xyz, int B, int N, int M, int start, const void *idx, const void *ws) {
-    if (!xyz || !idx || !ws) return FFPS_ERR_INVALID_ARG;
+int check_common(const void *xyz, int B, int N, int M, int start, const void *idx) {
+    if (!xyz || !idx) return FFPS_ERR_INVALID_ARG;
     if (B < 1 || N < 1 || M < 1 || M > N) return FFPS_ERR_INVALID_ARG;
     if (start < 0 || start >= N) return FFPS_ERR_INVALID_ARG;
     if ((long)B * N > (1L << 31) - 1) return FFPS_ERR_INVALID_ARG;
     return FFPS_OK;
 }
+
+// The helper kernels of FPS-Prune and of the stage chain put the cloud number
+// in gridDim.y, which the hardware limits to 65535.
+constexpr int kMaxBatchHelpers = 65535;
 
 // `variant` carries the kernel choice in its low byte and the optional
 // picks-per-round cap above it (FFPS_VARIANT_WITH_PICKS).
@@ -103,6 +128,7 @@ int resolve_variant(int B, int N, int variant, const Device &dev) {
     }
     if (v == FFPS_VARIANT_WG && N > wg_capacity()) return FFPS_ERR_UNSUPPORTED_SIZE;
     if (v == FFPS_VARIANT_GRID && N > grid_capacity(dev.num_cu)) return FFPS_ERR_UNSUPPORTED_SIZE;
+    if (v == FFPS_VARIANT_STREAM && N > stream_capacity()) return FFPS_ERR_UNSUPPORTED_SIZE;
     return v;
 }
 
@@ -230,7 +256,7 @@ int ffps_workspace_bytes(int B, int N, int M, size_t *bytes) {
 
 int ffps_exact(const float *d_xyz, int B, int N, int M, int start_idx, int variant, int32_t *d_idx,
                float *d_maxdist, void *d_ws, size_t ws_bytes, void *stream) {
-    int rc = check_common(d_xyz, B, N, M, start_idx, d_idx, d_ws);
+    int rc = d_ws ? check_common(d_xyz, B, N, M, start_idx, d_idx) : FFPS_ERR_INVALID_ARG;
     if (rc) return rc;
     if ((rc = check_variant(variant))) return rc;
     Workspace w = carve(B, N, M);
@@ -247,8 +273,9 @@ int ffps_exact(const float *d_xyz, int B, int N, int M, int start_idx, int varia
 int ffps_prune(const float *d_xyz, int B, int N, int M, int start_idx, int keep_num, int keep_den,
                unsigned flags, uint64_t seed, int variant, int32_t *d_idx, int *k_out_host,
                void *d_ws, size_t ws_bytes, void *stream) {
-    int rc = check_common(d_xyz, B, N, M, start_idx, d_idx, d_ws);
+    int rc = d_ws ? check_common(d_xyz, B, N, M, start_idx, d_idx) : FFPS_ERR_INVALID_ARG;
     if (rc) return rc;
+    if (B > kMaxBatchHelpers) return FFPS_ERR_INVALID_ARG;
     if ((rc = check_variant(variant))) return rc;
     int Nc, k, R;
     if ((rc = ffps_prune_sizes(N, M, keep_num, keep_den, flags, &Nc, &k, &R))) return rc;
@@ -268,8 +295,9 @@ int ffps_cached_stages(const float *d_xyz, int B, int N, int L, const int *M_sta
                        int keep_num, int keep_den, unsigned flags, uint64_t seed, int mode,
                        int variant, int32_t *d_idx, void *d_ws, size_t ws_bytes, void *stream) {
     if (!M_stages || L < 1) return FFPS_ERR_INVALID_ARG;
-    int rc = check_common(d_xyz, B, N, M_stages[0], start_idx, d_idx, d_ws);
+    int rc = d_ws ? check_common(d_xyz, B, N, M_stages[0], start_idx, d_idx) : FFPS_ERR_INVALID_ARG;
     if (rc) return rc;
+    if (B > kMaxBatchHelpers) return FFPS_ERR_INVALID_ARG;
     if ((rc = check_variant(variant))) return rc;
     if (mode != FFPS_MODE_CACHED && mode != FFPS_MODE_CHAIN) return FFPS_ERR_INVALID_ARG;
     long S = M_stages[0];
@@ -352,7 +380,7 @@ int ffps_last_status(const void *d_ws, void *stream) {
 int ffps_gather_rows(const float *d_rows, int B, int N, int C, const int32_t *d_idx, long idx_stride,
                      int S, float *d_out, void *stream) {
     if (!d_rows || !d_idx || !d_out) return FFPS_ERR_INVALID_ARG;
-    if (B < 1 || B > 65535 || N < 1 || C < 1 || S < 1 || idx_stride < S) return FFPS_ERR_INVALID_ARG;
+    if (B < 1 || B > kMaxBatchHelpers || N < 1 || C < 1 || S < 1 || idx_stride < S) return FFPS_ERR_INVALID_ARG;
     Device dev = query_device();
     if (dev.ok) return dev.ok;
     return hip_rc(launch_gather_rows(d_rows, B, N, C, d_idx, idx_stride, S, d_out, (hipStream_t)stream));
@@ -373,15 +401,16 @@ int ffps_barrier_probe(int iters, void *d_ws, size_t ws_bytes, void *stream, flo
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
         return FFPS_ERR_LAUNCH_FAILED;
     int G = dev.num_cu < kMaxGridWG ? dev.num_cu : kMaxGridWG;
-    hipEventRecord(e0, s);
-    hipError_t e = launch_barrier_probe((unsigned *)(ws + w.exchange), (int *)(ws + w.status), G, iters, s);
-    hipEventRecord(e1, s);
+    hipError_t e = hipEventRecord(e0, s);
+    if (e == hipSuccess)
+        e = launch_barrier_probe((unsigned *)(ws + w.exchange), (int *)(ws + w.status), G, iters, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
     float ms = 0.f;
     if (e != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
         hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
         rc = FFPS_ERR_LAUNCH_FAILED;
-    hipEventDestroy(e0);
-    hipEventDestroy(e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
     if (rc) return rc;
     *us_per_barrier = ms * 1000.f / (float)iters;
     int st = 0;

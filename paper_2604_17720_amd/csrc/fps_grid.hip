@@ -333,6 +333,7 @@ int units_of(int N, int g) {
 
 }  // namespace
 
+static_assert(kExchangeBytesPerCloud == 2 * buf_bytes(kT), "exchange area as the host side sizes it");
 size_t grid_exchange_bytes_per_cloud() { return 2 * buf_bytes(kT); }  // the streaming kernel reports two as well
 
 long grid_capacity(int num_cu) {

@@ -16,6 +16,7 @@ int wg_capacity();   // largest N the single-workgroup kernels hold
 int wgm_capacity();  // largest N of the multi-pick single-workgroup kernel
 int wg_units(int N);  // reporting units of the kernel that serves N points (0: one-pick kernel)
 int stream_workgroups(int N, int num_cu);  // workgroups the streaming kernel spreads N points over
+int stream_capacity();  // largest N the streaming kernel takes (its 32-bit point counters must not wrap)
 // In all FPS launchers `start_dev`, when not null, is a device array with one
 // start index per cloud that overrides `start` (read by the kernel).
 // `max_picks` caps the picks one pass over the points may deliver (0: no cap
@@ -27,7 +28,9 @@ hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, const
 
 // ---- fps_grid.hip: clouds spread over the whole device, resident in registers ----
 constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a launch may use
-size_t grid_exchange_bytes_per_cloud();  // bytes of one cloud's exchange area (two record buffers)
+// bytes of one cloud's exchange area: two buffers of four 16-byte chunks for each of 256 units
+constexpr size_t kExchangeBytesPerCloud = 2 * 4 * (size_t)kMaxGridWG * 16;
+size_t grid_exchange_bytes_per_cloud();  // the same value, as the kernels' own headers derive it
 long grid_capacity(int num_cu);          // largest N the register-resident grid kernel holds
 // How B clouds of N points are laid over the device: workgroups per cloud, and
 // how many clouds one launch carries (each cloud on its own cluster of workgroups).

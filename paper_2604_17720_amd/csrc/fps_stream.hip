@@ -199,6 +199,10 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
 
 }  // namespace
 
+// A lane's position advances by 8192 points per step and a slice end is
+// computed as slice begin + slice length, both in 32-bit integers.
+int stream_capacity() { return 0x7fffffff - 2 * kStreamThreads * 4 - 4 * kMaxGridWG; }
+
 int stream_workgroups(int N, int num_cu) {
     int maxG = num_cu < kMaxGridWG ? num_cu : kMaxGridWG;
     // a workgroup pass covers 4096 points per step; do not spread thinner than that

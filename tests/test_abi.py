@@ -107,6 +107,15 @@ def test_entry_points_validate_before_touching_the_device():
     assert stages([50], mode=2) == fb.FFPS_ERR_INVALID_ARG
     assert stages([50], L_=0) == fb.FFPS_ERR_INVALID_ARG
 
+    # The helper kernels of FPS-Prune and the stage chain carry the cloud number in
+    # gridDim.y: more than 65535 clouds are refused before anything is enqueued.
+    arr = (ctypes.c_int * 1)(2)
+    assert L.ffps_prune(fake, 65536, 4, 2, 0, 1, 1, 3, 0, 0, fake, ctypes.byref(k), fake, big,
+                        null) == fb.FFPS_ERR_INVALID_ARG
+    assert L.ffps_cached_stages(fake, 65536, 4, 1, arr, 0, 1, 1, 0, 0, 0, 0, fake, fake, big,
+                                null) == fb.FFPS_ERR_INVALID_ARG
+    assert L.ffps_gather_rows(fake, 65536, 4, 3, fake, 2, 2, fake, null) == fb.FFPS_ERR_INVALID_ARG
+
 
 def test_plan_of_the_five_configurations_and_its_limits():
     """Host logic behind FFPS_VARIANT_AUTO on a 256-CU device: which kernel runs,
@@ -125,6 +134,11 @@ def test_plan_of_the_five_configurations_and_its_limits():
     assert plan(1, 4608)[0] == WG and plan(1, 4609)[0] == GRID
     assert plan(1, 256 * 12288)[0] == GRID and plan(1, 256 * 12288 + 1)[0] == STREAM
     assert plan(1, 1 << 25) == (STREAM, 256, 256, 1)
+    # the streaming kernel counts points in 32-bit integers and steps by 8192
+    assert plan(1, 2 ** 31 - 1 - 8192 - 1024)[0] == STREAM
+    with pytest.raises(fb.FlashFPSError) as e:
+        plan(1, 2 ** 31 - 1 - 8192 - 1023)
+    assert e.value.code == fb.FFPS_ERR_UNSUPPORTED_SIZE
     # explicit variants and their size limits
     assert plan(4, 20000, WG) == (WG, 1, 0, 4)
     with pytest.raises(fb.FlashFPSError) as e:
