@@ -109,6 +109,28 @@ int ffps_exact(const float *d_xyz, int B, int N, int M, int start_idx, int varia
                int32_t *d_idx, float *d_maxdist, void *d_ws, size_t ws_bytes, void *stream);
 
 /*
+ * ffps_exact for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): takes
+ * no workspace and allocates nothing.  What the kernels need besides inputs and
+ * outputs (the status block and the exchange areas of one launch, 8 MiB + 256
+ * bytes) lives in an array inside the library's device image; every GPU the
+ * library runs on holds its copy until the process ends.
+ *   arguments   as ffps_exact, without d_ws / ws_bytes
+ *   d_status    out  int32[2] on the device, or NULL: {status word, rounds} of
+ *                    this call, readable through ffps_last_status(d_status, stream)
+ *                    and ffps_last_rounds(d_status, stream)
+ * Limit: clouds must fit the register-resident kernels, N <= 12288 points per CU
+ * (3,145,728 on MI355X); beyond that, or with FFPS_VARIANT_STREAM, the call
+ * returns FFPS_ERR_UNSUPPORTED_SIZE and enqueues nothing.  B is not limited.
+ * All calls on one GPU share that GPU's array (each call clears what it needs
+ * at the start): calls that may run at the same time on one GPU, on whatever
+ * streams, race and must be serialised by the caller.  The outputs equal
+ * ffps_exact's bit for bit.
+ */
+int ffps_exact_noalloc(const float *d_xyz, int B, int N, int M, int start_idx, int variant,
+                       int32_t *d_idx, float *d_maxdist, int32_t *d_status, void *stream);
+
+/*
  * FPS-Prune (Sec. 3.2; Alg. 1, layer 1).  With (N', k, R) = ffps_prune_sizes:
  *   candidates  the N' indices sort{ (start_idx + floor(j*N/N')) mod N : j < N' }
  *               (an index-uniform subsample that contains start_idx);

@@ -37,7 +37,8 @@ def variant_with_picks(variant: int, picks: int) -> int:
 
 EXPORTS = ["ffps_version", "ffps_strerror", "ffps_prune_sizes", "ffps_workspace_bytes",
            "ffps_exact", "ffps_prune", "ffps_cached_stages", "ffps_last_status",
-           "ffps_last_rounds", "ffps_barrier_probe", "ffps_gather_rows", "ffps_describe_plan"]
+           "ffps_last_rounds", "ffps_barrier_probe", "ffps_gather_rows", "ffps_describe_plan",
+           "ffps_exact_noalloc"]
 
 
 class FlashFPSError(RuntimeError):
@@ -65,6 +66,7 @@ def lib() -> ctypes.CDLL:
         L.ffps_prune_sizes.argtypes = [c_int, c_int, c_int, c_int, ctypes.c_uint, ip, ip, ip]
         L.ffps_workspace_bytes.argtypes = [c_int, c_int, c_int, ctypes.POINTER(c_sz)]
         L.ffps_exact.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_sz, c_vp]
+        L.ffps_exact_noalloc.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
         L.ffps_prune.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, ctypes.c_uint,
                                  ctypes.c_uint64, c_int, c_vp, ip, c_vp, c_sz, c_vp]
         L.ffps_cached_stages.argtypes = [c_vp, c_int, c_int, c_int, ip, c_int, c_int, c_int,
@@ -178,6 +180,23 @@ def ffps_exact(xyz, M, start_idx=0, variant=FFPS_VARIANT_AUTO, return_maxdist=Fa
     if rc:
         raise FlashFPSError(rc, "ffps_exact")
     return (idx, md) if return_maxdist else idx
+
+
+def ffps_exact_noalloc(xyz, M, out, start_idx=0, variant=FFPS_VARIANT_AUTO, out_maxdist=None,
+                       out_status=None, stream=None):
+    """ffps_exact without a workspace and without any allocation: the caller
+    passes every output (out int32 [B,M]; optionally out_maxdist fp32 [B,M] and
+    out_status int32 [2]).  Returns out."""
+    torch, x, B, N = _prep(xyz)
+    if not (1 <= M <= N):
+        raise FlashFPSError(FFPS_ERR_INVALID_ARG, "ffps_exact_noalloc")
+    rc = lib().ffps_exact_noalloc(x.data_ptr(), B, N, M, start_idx, variant, out.data_ptr(),
+                                  out_maxdist.data_ptr() if out_maxdist is not None else None,
+                                  out_status.data_ptr() if out_status is not None else None,
+                                  _stream(torch, stream))
+    if rc:
+        raise FlashFPSError(rc, "ffps_exact_noalloc")
+    return out
 
 
 def ffps_prune(xyz, M, keep_num, keep_den, flags=FFPS_FLAG_CP | FFPS_FLAG_IP, start_idx=0,

@@ -48,6 +48,16 @@ std::mutex g_device_mutex;
 bool g_device_known[kMaxDevices];
 Device g_device[kMaxDevices];
 
+// Device memory of the allocation-free entry point: the status block and the
+// exchange areas of one launch, i.e. everything exact FPS needs besides its
+// inputs and outputs as long as the clouds fit in registers.  Every device the
+// library runs on holds its own copy of this array until the process ends.  In
+// host code the name is only a handle: the array's address on a device comes
+// from hipGetSymbolAddress, asked once per device with that device current.
+constexpr size_t kScratchBytes = kAlign + (size_t)kMaxGridWG * kExchangeBytesPerCloud;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+char *g_scratch_ptr[kMaxDevices];  // address of `scratch` on each device, null until asked
+
 Device query_device_uncached(int dev) {
     Device d{FFPS_ERR_LAUNCH_FAILED, 0};
     hipDeviceProp_t p;
@@ -74,6 +84,18 @@ Device query_device(int *dev_out = nullptr) {
         g_device_known[dev] = g_device[dev].ok != FFPS_ERR_LAUNCH_FAILED;
     }
     return g_device[dev];
+}
+
+// Address of `scratch` on the current device (number `dev`), or null.
+char *scratch_of_current_device(int dev) {
+    if (dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_device_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = (char *)p;
+    }
+    return g_scratch_ptr[dev];
 }
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? FFPS_OK : FFPS_ERR_LAUNCH_FAILED; }
@@ -268,6 +290,32 @@ int ffps_exact(const float *d_xyz, int B, int N, int M, int start_idx, int varia
     if ((rc = clear_status((char *)d_ws, w, s))) return rc;
     return run_exact(d_xyz, B, N, M, start_idx, nullptr, variant, d_idx, M, d_maxdist, M,
                      (char *)d_ws, w, dev, s);
+}
+
+int ffps_exact_noalloc(const float *d_xyz, int B, int N, int M, int start_idx, int variant,
+                       int32_t *d_idx, float *d_maxdist, int32_t *d_status, void *stream) {
+    int dev_no = 0;
+    int rc = check_common(d_xyz, B, N, M, start_idx, d_idx);
+    if (rc) return rc;
+    if ((rc = check_variant(variant))) return rc;
+    Device dev = query_device(&dev_no);
+    if (dev.ok) return dev.ok;
+    if ((rc = resolve_variant(B, N, variant, dev)) < 0) return rc;
+    // the streaming kernel needs N running distances per cloud: beyond this array
+    if (rc == FFPS_VARIANT_STREAM) return FFPS_ERR_UNSUPPORTED_SIZE;
+    char *ws = scratch_of_current_device(dev_no);
+    if (!ws) return FFPS_ERR_LAUNCH_FAILED;
+    Workspace w;
+    const size_t none = ~(size_t)0;
+    w.status = 0; w.exchange = kAlign; w.total = kScratchBytes;
+    w.cxyz = w.loc = w.bitmap = w.mind = w.cand = w.spos = none;  // not part of this path
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = clear_status(ws, w, s))) return rc;
+    rc = run_exact(d_xyz, B, N, M, start_idx, nullptr, variant, d_idx, M, d_maxdist, M, ws, w, dev, s);
+    if (rc) return rc;
+    if (d_status)
+        rc = hip_rc(launch_copy_prefix((const int32_t *)(ws + w.status), 2, 1, 2, d_status, 2, s));
+    return rc;
 }
 
 int ffps_prune(const float *d_xyz, int B, int N, int M, int start_idx, int keep_num, int keep_den,
