@@ -23,7 +23,7 @@ FLAG_PERM = 4
 MODE_CACHED = 0
 MODE_CHAIN = 1
 
-CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC", "-std=c11"]
+CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC", "-std=gnu11", "-pthread"]
 
 
 def build(force: bool = False) -> str:
@@ -45,6 +45,8 @@ def _load():
         ci = ctypes.c_int
         lib.oracle_fps_exact.argtypes = [fp, ci, ci, ci, ip, fp]
         lib.oracle_fps_exact.restype = ci
+        lib.oracle_fps_exact_mt.argtypes = [fp, ci, ci, ci, ip, fp, ci]
+        lib.oracle_fps_exact_mt.restype = ci
         lib.oracle_prune_sizes.argtypes = [ci, ci, ci, ci, ctypes.c_uint,
                                            ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
         lib.oracle_prune_sizes.restype = ci
@@ -105,6 +107,29 @@ def fps_exact(xyz, M, start=0, return_maxdist=False):
     """Exact FPS (Eq. 1).  xyz [N,3] or [B,N,3]; returns int32 idx [M] or [B,M]
     (and the squared pick distances when return_maxdist)."""
     return _batched(_fps_exact1, xyz, M, start, return_maxdist)
+
+
+def host_threads() -> int:
+    """Threads the all-cores run may use: the cores this process may run on,
+    capped by OMP_NUM_THREADS when that is set."""
+    n = len(os.sched_getaffinity(0))
+    env = os.environ.get("OMP_NUM_THREADS", "")
+    if env.isdigit() and int(env) >= 1:
+        n = min(n, int(env))
+    return max(1, n)
+
+
+def fps_exact_mt(xyz, M, start=0, threads=None, return_maxdist=False):
+    """Exact FPS of ONE cloud on `threads` host threads (default host_threads());
+    identical to fps_exact for any thread count."""
+    a = _cloud(xyz)
+    idx = np.empty(M, dtype=np.int32)
+    md = np.empty(M, dtype=np.float32)
+    t = host_threads() if threads is None else int(threads)
+    rc = _load().oracle_fps_exact_mt(_fptr(a), a.shape[0], M, start, _iptr(idx), _fptr(md), t)
+    if rc:
+        raise ValueError(f"oracle_fps_exact_mt: invalid arguments (rc={rc})")
+    return (idx, md) if return_maxdist else idx
 
 
 def prune_sizes(N, M, keep_num, keep_den, flags):

@@ -363,3 +363,157 @@ double oracle_coverage_radius(const float *xyz, int N, const int32_t *sel, int S
     }
     return sqrt((double)worst);
 }
+
+/*
+ * Exact FPS on several host threads: the same loop as oracle_fps_exact with the
+ * points of each iteration divided into `nthreads` contiguous chunks.  Every
+ * thread refreshes the minimum distances of its chunk and finds the chunk's
+ * best point (largest value, lowest index: strict > in ascending order);
+ * after a barrier every thread merges the chunk results in ascending chunk
+ * order with the same strict >, which again keeps the lowest index among equal
+ * values.  Per-point arithmetic is that of the single-thread loop, so the
+ * result is identical to it for any number of threads (asserted by the tests).
+ * Exists for the all-cores CPU baseline of the benchmark; the single-thread
+ * function above stays the reference statement of the method.
+ */
+#include <pthread.h>
+#include <sched.h>
+#include <stdatomic.h>
+
+typedef struct {
+    atomic_int count;
+    atomic_int sense;
+    int n;
+} spin_barrier;
+
+static void spin_barrier_wait(spin_barrier *b, int *local_sense)
+{
+    *local_sense = !*local_sense;
+    if (atomic_fetch_add(&b->count, 1) == b->n - 1) {
+        atomic_store(&b->count, 0);
+        atomic_store(&b->sense, *local_sense);
+    } else {
+        int spins = 0;
+        while (atomic_load(&b->sense) != *local_sense)
+            if (++spins > 2000) /* more threads than free cores: let the others run */
+                sched_yield();
+    }
+}
+
+typedef struct {
+    float d;
+    int i;
+    char pad[56]; /* one cache line per slot */
+} chunk_best;
+
+typedef struct {
+    const float *xyz;
+    float *mind;
+    int N, M, start;
+    int32_t *idx;
+    float *maxdist;
+    int nthreads;
+    chunk_best *slots; /* [2][nthreads], alternating by iteration parity */
+    spin_barrier bar;
+} mt_shared;
+
+typedef struct {
+    mt_shared *sh;
+    int t;
+} mt_arg;
+
+static void *mt_worker(void *p)
+{
+    mt_arg *a = (mt_arg *)p;
+    mt_shared *sh = a->sh;
+    const int T = sh->nthreads, t = a->t;
+    const int lo = (int)((int64_t)sh->N * t / T), hi = (int)((int64_t)sh->N * (t + 1) / T);
+    const float *xyz = sh->xyz;
+    float *mind = sh->mind;
+    int sense = 0;
+    for (int i = lo; i < hi; ++i)
+        mind[i] = INFINITY;
+    int last = sh->start;
+    for (int k = 1; k < sh->M; ++k) {
+        const float *q = xyz + 3 * (size_t)last;
+        int best = -1;
+        float bestd = 0.0f;
+        for (int i = lo; i < hi; ++i) {
+            float d = sqdist(xyz + 3 * (size_t)i, q);
+            if (d < mind[i])
+                mind[i] = d;
+            if (best < 0 || mind[i] > bestd) {
+                best = i;
+                bestd = mind[i];
+            }
+        }
+        chunk_best *slot = sh->slots + (size_t)(k & 1) * T;
+        slot[t].d = bestd;
+        slot[t].i = best; /* -1: empty chunk */
+        spin_barrier_wait(&sh->bar, &sense);
+        best = -1;
+        bestd = 0.0f;
+        for (int c = 0; c < T; ++c)
+            if (slot[c].i >= 0 && (best < 0 || slot[c].d > bestd)) {
+                best = slot[c].i;
+                bestd = slot[c].d;
+            }
+        if (t == 0) {
+            sh->idx[k] = best;
+            if (sh->maxdist)
+                sh->maxdist[k] = bestd;
+        }
+        last = best;
+    }
+    return NULL;
+}
+
+int oracle_fps_exact_mt(const float *xyz, int N, int M, int start, int32_t *idx, float *maxdist,
+                        int nthreads)
+{
+    if (!xyz || !idx || N < 1 || M < 1 || M > N || start < 0 || start >= N || nthreads < 1 ||
+        nthreads > 1024)
+        return -1;
+    mt_shared sh;
+    sh.xyz = xyz;
+    sh.N = N;
+    sh.M = M;
+    sh.start = start;
+    sh.idx = idx;
+    sh.maxdist = maxdist;
+    sh.nthreads = nthreads;
+    atomic_init(&sh.bar.count, 0);
+    atomic_init(&sh.bar.sense, 0);
+    sh.bar.n = nthreads;
+    sh.mind = (float *)malloc((size_t)N * sizeof(float));
+    sh.slots = (chunk_best *)malloc((size_t)2 * nthreads * sizeof(chunk_best));
+    pthread_t *th = (pthread_t *)malloc((size_t)nthreads * sizeof(pthread_t));
+    mt_arg *args = (mt_arg *)malloc((size_t)nthreads * sizeof(mt_arg));
+    int rc = -2;
+    if (sh.mind && sh.slots && th && args) {
+        idx[0] = start;
+        if (maxdist)
+            maxdist[0] = INFINITY;
+        int made = 0;
+        for (; made < nthreads; ++made) {
+            args[made].sh = &sh;
+            args[made].t = made;
+            if (pthread_create(&th[made], NULL, mt_worker, &args[made]))
+                break;
+        }
+        if (made == nthreads) {
+            rc = 0;
+        } else {
+            /* the barrier would wait for the missing threads for ever: this cannot
+             * be recovered without them, so treat it as fatal for the process */
+            abort();
+        }
+        for (int t = 0; t < made; ++t)
+            pthread_join(th[t], NULL);
+    }
+    free(sh.mind);
+    free(sh.slots);
+    free(th);
+    free(args);
+    return rc;
+}

@@ -100,6 +100,40 @@ def test_brute_force_float32(oracle):
         assert oracle.fps_exact(x, m, start).tolist() == brute_fps_f32(x, m, start)
 
 
+@pytest.mark.parametrize("threads", [1, 2, 3, 5, 8, 13])
+def test_threaded_exact_fps(oracle, threads):
+    """The all-cores entry (point chunks per iteration, chunk results merged in
+    ascending chunk order) against the same pins as the single-thread loop:
+    hand-worked sequences, the exact-integer brute force on tie-heavy lattices
+    (chunks smaller than the thread count included), and equality with the
+    single-thread run, indices and distance bits, on every kind of cloud."""
+    for name, cloud in (("collinear9.txt", inputs.lattice_line(9)), ("grid3x3.txt", inputs.lattice_grid(3, 3))):
+        idx, md = _read_golden(name)
+        got, gmd = oracle.fps_exact_mt(cloud, len(idx), 0, threads, return_maxdist=True)
+        assert got.tolist() == idx.tolist() and np.array_equal(gmd, md)
+    rng = np.random.default_rng(70 + threads)
+    for trial in range(25):
+        side = int(rng.integers(2, 5))
+        n = int(rng.integers(2, side ** 3 + 1))
+        cells = rng.permutation(side ** 3)[:n]
+        pts = np.stack([cells // (side * side), (cells // side) % side, cells % side], axis=1)
+        start = int(rng.integers(0, n))
+        sel, vals = brute_fps_int(pts, n, start)
+        got, gmd = oracle.fps_exact_mt(pts.astype(np.float32), n, start, threads, return_maxdist=True)
+        assert got.tolist() == sel and [int(v) for v in gmd[1:]] == vals[1:]
+    clouds = [inputs.uniform_cube(1, 1), inputs.uniform_cube(7, 2), inputs.make_config(4, N=20011)[0],
+              inputs.lattice_grid(17, 13, 5), np.repeat(inputs.lattice_grid(4, 4, 4), 3, axis=0),
+              inputs.planes_and_clusters(5003, 9)]
+    for x in clouds:
+        n = x.shape[0]
+        m, start = min(n, 400), n // 3
+        a, amd = oracle.fps_exact(x, m, start, return_maxdist=True)
+        b, bmd = oracle.fps_exact_mt(x, m, start, threads, return_maxdist=True)
+        assert np.array_equal(a, b) and np.array_equal(amd.view(np.uint32), bmd.view(np.uint32))
+    with pytest.raises(ValueError):
+        oracle.fps_exact_mt(clouds[1], 3, 0, 0)
+
+
 def test_each_pick_maximises_min_distance_in_float64(oracle):
     """Property from Eq. 1, checked in float64 so it does not depend on the
     fp32 rounding of either side: every pick attains the maximum of the
