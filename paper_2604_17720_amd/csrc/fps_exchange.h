@@ -33,6 +33,7 @@ constexpr int kSpinLimit = 1 << 19;
 constexpr uint32_t kNoIndex = 0x7fffffffu;  // index of a candidate that does not exist
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // Exchange area: two buffers (round parity); each holds one array of 256 slots
 // x 16 bytes per chunk of a record.  A record of T candidates is, in chunks of
@@ -63,8 +64,12 @@ __device__ __forceinline__ bool chunk_ok(const u32x4 &c, uint32_t round, uint32_
 // Device-scope (all XCDs) 16-byte store and loads.  The compiler offers atomics
 // up to 8 bytes only, so these are spelled out; sc1 is the device-scope cache
 // policy the compiler itself uses for agent-scope atomics on this target.
+// A vector-memory store of more than 8 bytes reads its data registers a few
+// cycles after it issues, and a vector instruction that overwrites them right
+// behind it changes what is stored.  The compiler keeps the distance for its
+// own stores but cannot see into this text, hence the two idle cycles.
 __device__ __forceinline__ void store_chunk(void *p, u32x4 v) {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
 // r[c][q] = 16 bytes at p + c * kChunkBytes + q * 1024, q < 4: all loads are
 // issued before the single wait, so a poll costs one round trip.
@@ -147,16 +152,51 @@ __device__ __forceinline__ u32x4 lds_read16(uint32_t off) {
     return r;
 }
 
-// The same read in two halves, so that work can overlap its latency: r is not
-// valid before lds_wait16(r) has run.
-__device__ __forceinline__ void lds_issue16(u32x4 &r, uint32_t off) {
-    asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(off) : "memory");
+// Two 16-byte reads in flight together, complete on return.
+__device__ __forceinline__ void lds_read16x2(u32x4 &a, u32x4 &b, uint32_t off_a, uint32_t off_b) {
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(a), "=&v"(b) : "v"(off_a), "v"(off_b) : "memory");
 }
-__device__ __forceinline__ void lds_wait16(u32x4 &r) {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r) : : "memory");
+// Four consecutive 16-byte words (64 bytes from `off`), complete on return.
+__device__ __forceinline__ void lds_read64(u32x4 &a, u32x4 &b, u32x4 &c, u32x4 &d, uint32_t off) {
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:16\n\t"
+                 "ds_read_b128 %2, %4 offset:32\n\tds_read_b128 %3, %4 offset:48\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(a), "=&v"(b), "=&v"(c), "=&v"(d) : "v"(off) : "memory");
+}
+// Eight consecutive 16-byte words (128 bytes from `off`), complete on return.
+__device__ __forceinline__ void lds_read128(u32x4 (&r)[8], uint32_t off) {
+    asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:16\n\t"
+                 "ds_read_b128 %2, %8 offset:32\n\tds_read_b128 %3, %8 offset:48\n\t"
+                 "ds_read_b128 %4, %8 offset:64\n\tds_read_b128 %5, %8 offset:80\n\t"
+                 "ds_read_b128 %6, %8 offset:96\n\tds_read_b128 %7, %8 offset:112\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]),
+                   "=&v"(r[6]), "=&v"(r[7])
+                 : "v"(off) : "memory");
+}
+// The records of two candidates, their values (each with the value that follows
+// it in the array) and their indices, with all reads in flight together.
+__device__ __forceinline__ void lds_read_pair(u32x4 &c0, u32x4 &c1, u32x2 &v0, u32x2 &v1, uint32_t &i0,
+                                              uint32_t &i1, uint32_t a_c0, uint32_t a_c1, uint32_t a_v0,
+                                              uint32_t a_v1, uint32_t a_i0, uint32_t a_i1) {
+    asm volatile("ds_read_b128 %0, %6\n\tds_read_b128 %1, %7\n\t"
+                 "ds_read2_b32 %2, %8 offset1:1\n\tds_read2_b32 %3, %9 offset1:1\n\t"
+                 "ds_read_b32 %4, %10\n\tds_read_b32 %5, %11\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(c0), "=&v"(c1), "=&v"(v0), "=&v"(v1), "=&v"(i0), "=&v"(i1)
+                 : "v"(a_c0), "v"(a_c1), "v"(a_v0), "v"(a_v1), "v"(a_i0), "v"(a_i1)
+                 : "memory");
+}
+__device__ __forceinline__ void lds_write4(uint32_t off, uint32_t v) {
+    asm volatile("ds_write_b32 %0, %1" : : "v"(off), "v"(v) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_read4(uint32_t off) {
+    uint32_t r;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(off) : "memory");
+    return r;
 }
 // 8-byte LDS word written and read by one instruction each.
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void lds_write8(uint32_t off, u32x2 v) {
     asm volatile("ds_write_b64 %0, %1" : : "v"(off), "v"(v) : "memory");
 }
@@ -236,20 +276,23 @@ struct RoundInput {
 
 // LDS used by the wave that runs exchange_round.
 struct RoundLds {
-    __attribute__((aligned(16))) u32x4 pk[kMaxPicksPerRound];  // picks of the round: {x, y, z, seq}
-    uint32_t pk_idx[kMaxPicksPerRound];  // index of each pick of the round
+    // picks of the round: {x, y, z, seq}; three spare slots that are never picks,
+    // so that readers may always read a slot and the three behind it
+    __attribute__((aligned(16))) u32x4 pk[kMaxPicksPerRound + 3];
+    uint32_t pk_idx[kMaxPicksPerRound];  // index of each pick of the round (general replay loop)
     uint32_t pk_val[kMaxPicksPerRound];  // and the value it was picked with
-    uint32_t pk_key[kMaxPicksPerRound];  // winning key of each pick (packed replay loops)
-    uint32_t tab_idx[2 * kWave];         // point index by candidate code (packed replay loops)
-    __attribute__((aligned(16))) u32x4 cmp_a[2 * kWave];  // compacted live candidates: {value, index, x, y}
-    float cmp_z[2 * kWave];                               // and z
+    // live candidates, first in compaction order, then in the order of the replay:
+    __attribute__((aligned(16))) u32x4 cand[2 * kWave + 3];  // {x, y, z, value; later sequence number}; spare entries for reads ahead
+    __attribute__((aligned(16))) uint32_t keyw[2 * kWave + 32];  // 32-bit sort keys, zero-padded; later the values in order
+    // (entries cand[130], keyw[130], idxw[130] take what the compaction discards)
+    uint32_t idxw[2 * kWave + 3];                                // point indices
 };
 
 // Counters of a profiling build (workgroup 0 only).
 struct RoundProf {
-    uint32_t acc[8];   // 100 MHz ticks per phase; [5], [6]: rounds on the packed paths; [7]: polls
-    uint32_t loop[4];  // shader cycles and picks inside the two packed loops
-    uint32_t sub[4];   // shader cycles of the replay set-up: bounds, counting, compaction
+    uint32_t acc[8];   // 100 MHz ticks per phase; [5], [6]: rounds of the ordered replay with up to 64 / more candidates; [7]: polls
+    uint32_t loop[4];  // shader cycles and picks inside the ordered replay's pick loop, by the same split
+    uint32_t sub[4];   // shader cycles of the replay set-up: bounds, counting, compaction, ordering
     uint64_t last;
 };
 #ifdef FFPS_PROFILE
@@ -267,6 +310,62 @@ struct RoundProf {
     } while (0)
 #endif
 
+// The inner loop of the ordered replay, for one set of candidates (lane L holds
+// candidate L of the set: current value v, coordinates x, y, z; `o` is the value
+// it had at the start of the round, or 0xffffffff for a lane at which the run
+// must end; `seq` is the sequence number the candidate has as a pick and `a_pk`
+// the address of the LDS slot it goes to, both per lane).  Starting at candidate
+// i, with `bit` = 1 << i, for as long as candidate i's value is unchanged (v ==
+// o in lane i): lane i alone writes its record {x, y, z, seq} to its slot for the
+// worker waves, its coordinates are read out of the lane, every lane's value is
+// lowered by the squared distance to it, and i steps on.  `bit` runs off the top
+// after lane 63, which ends the run as well.  Returns with i and `bit` at the
+// first candidate that was not handed over (bit 0: the set is used up).
+// 21 instructions per pick and nothing to wait for: LDS is only written.  The
+// registers named in the text are scratch of this block; distances are the
+// individually rounded operations of sqdist; a lane read into a scalar register
+// needs two instructions before a vector instruction may use it, which the
+// order of the reads provides.
+__device__ __forceinline__ void ordered_run(uint32_t &v, uint32_t o, float x, float y, float z,
+                                            uint32_t seq, uint32_t a_pk, uint64_t &bit, int &i) {
+    uint32_t sx, sy, sz;
+#define FFPS_STEP(EXIT)                                   \
+    "v_cmp_eq_u32 vcc, %[v], %[o]\n\t"                     \
+    "s_and_b64 vcc, vcc, %[bit]\n\t"                       \
+    "s_cbranch_scc0 " EXIT "\n\t"                          \
+    "s_mov_b64 exec, vcc\n\t"                              \
+    "ds_write_b128 %[ap], v[108:111]\n\t"                  \
+    "s_mov_b64 exec, -1\n\t"                               \
+    "v_readlane_b32 %[sx], %[x], %[i]\n\t"                 \
+    "v_readlane_b32 %[sy], %[y], %[i]\n\t"                 \
+    "v_readlane_b32 %[sz], %[z], %[i]\n\t"                 \
+    "v_subrev_f32 v112, %[sx], %[x]\n\t"                   \
+    "v_subrev_f32 v113, %[sy], %[y]\n\t"                   \
+    "v_subrev_f32 v114, %[sz], %[z]\n\t"                   \
+    "v_mul_f32 v112, v112, v112\n\t"                       \
+    "v_mul_f32 v113, v113, v113\n\t"                       \
+    "v_mul_f32 v114, v114, v114\n\t"                       \
+    "v_add_f32 v112, v112, v113\n\t"                       \
+    "v_add_f32 v112, v112, v114\n\t"                       \
+    "v_min_f32 %[v], %[v], v112\n\t"                       \
+    "s_lshl_b64 %[bit], %[bit], 1\n\t"                     \
+    "s_add_i32 %[i], %[i], 1\n\t"
+    asm volatile(
+        "v_mov_b32 v108, %[x]\n\t"
+        "v_mov_b32 v109, %[y]\n\t"
+        "v_mov_b32 v110, %[z]\n\t"
+        "v_mov_b32 v111, %[seq]\n\t"
+        "1:\n\t"
+        FFPS_STEP("9f")
+        FFPS_STEP("9f")
+        "s_branch 1b\n\t"
+        "9:\n\t"
+        : [v] "+v"(v), [bit] "+s"(bit), [i] "+s"(i), [sx] "=&s"(sx), [sy] "=&s"(sy), [sz] "=&s"(sz)
+        : [o] "v"(o), [x] "v"(x), [y] "v"(y), [z] "v"(z), [seq] "v"(seq), [ap] "v"(a_pk)
+        : "memory", "vcc", "scc", "v108", "v109", "v110", "v111", "v112", "v113", "v114");
+#undef FFPS_STEP
+}
+
 // Replay of the greedy rule of Eq. 1 on KC candidates per lane of ONE full wave
 // (value bits cv, point index ci, coordinates cx/cy/cz; a candidate that does
 // not exist has value 0 and index kNoIndex), given lb = the lane's share of the
@@ -278,8 +377,11 @@ struct RoundProf {
 // candidate arrays are used up.
 struct RoundResult {
     int cnt;        // picks of the round, or -1 when the round failed
-    bool by_key;    // picks noted as keys (L.pk_key, L.tab_idx) rather than in L.pk_idx / L.pk_val
-    uint32_t T;     // threshold the keys are relative to
+    bool by_lane;   // picks noted in the lanes (below) rather than in L.pk_idx / L.pk_val
+    // by_lane: what this lane's two candidates of the ordered replay became: pick
+    // number within the round (-1: not picked), point index, value when picked
+    int pc[2];
+    uint32_t pi[2], pv[2];
 };
 
 // Writes index (and value) of the picks of a round to the outputs; run by the
@@ -379,181 +481,204 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             count_live();
         }
     }
-    // With at most 128 live candidates whose values lie within 2^24 ulps above
-    // the threshold, value and position fit one 32-bit key
-    //   key = (value_bits - threshold_bits) << 7 | position,
-    // and a single wave-wide max yields the best value and a lane that holds it.
-    // Values at or below the threshold saturate to 0 and end the round.  Whether other
-    // candidates hold the same value costs one ballot; only then is the index
-    // compared.
-    const bool packed = total >= 1 && total <= 2 * kWave && V - T < (1u << 24);
+    // With at most 128 live candidates the replay needs no argmax per pick.  Put
+    // the candidates in the order (value descending, index ascending).  The first
+    // one is the next pick.  Picking a point can only lower other values, so the
+    // next candidate in that order is the following pick as long as its own value
+    // has not been lowered by a pick of this round: everything behind it started
+    // no higher and has not grown, candidates ahead of it are picked or gone, and
+    // unreported points are at or below the threshold.  A candidate whose value
+    // has been lowered to the threshold or below is out of this round and is
+    // passed over; one that has been lowered but is still above the threshold
+    // may now belong further back in the order, and the round ends before it
+    // (the next round sees it with its new value).  Per pick this costs the
+    // distance update of the candidates and one comparison.
+    const bool ordered = total >= 1 && total <= 2 * kWave;
     FFPS_SUB(1);
 #ifdef FFPS_PROFILE
-    if (prof && packed) prof->acc[total <= kWave ? 5 : 6] += 1;
+    if (prof && ordered) prof->acc[total <= kWave ? 5 : 6] += 1;
 #endif
-    if (packed) {
-        int pos = before;
+    RoundResult res;
+    res.pc[0] = res.pc[1] = -1;
+    res.pi[0] = res.pi[1] = kNoIndex;
+    res.pv[0] = res.pv[1] = 0u;
+    if (ordered) {
+        const uint32_t cand_off = lds_offset(L.cand), key_off = lds_offset(L.keyw),
+                       idx_off = lds_offset(L.idxw);
+        // 32-bit sort key of a live candidate: its value above the threshold and its
+        // compaction position, (value - T) << 7 | position, which orders by value
+        // and is unique.  Candidates of equal value come out in position order
+        // rather than index order; that is detected below and then put right.
+        const bool narrow = V - T < (1u << 24);
+        // compaction without branches: a candidate that is not live goes to a slot
+        // behind the live ones, which nobody reads
+        {
+            const uint32_t dump = (uint32_t)(2 * kWave + 2);
+            uint32_t pos = (uint32_t)before;
 #pragma unroll
-        for (int q = 0; q < KC; ++q) {
-            if (cv[q] > T) {
+            for (int q = 0; q < KC; ++q) {
+                const bool live = cv[q] > T;
+                const uint32_t at = live ? pos : dump;
                 u32x4 r;
-                r.x = cv[q]; r.y = ci[q]; r.z = f2u(cx[q]); r.w = f2u(cy[q]);
-                L.cmp_a[pos] = r;
-                L.cmp_z[pos] = cz[q];
-                ++pos;
+                r.x = f2u(cx[q]); r.y = f2u(cy[q]); r.z = f2u(cz[q]); r.w = cv[q];
+                lds_write16(cand_off + at * 16, r);
+                lds_write4(key_off + at * 4, ((cv[q] - T) << 7) | pos);
+                lds_write4(idx_off + at * 4, ci[q]);
+                pos += live ? 1u : 0u;
             }
         }
+        if (lane < 32) lds_write4(key_off + (total + lane) * 4, 0u);  // padding: below every key
         // the same wave wrote and now reads: LDS keeps its accesses in order
         FFPS_SUB(2);
-        // In both loops below the key of a candidate is (value - T) << 7 | code,
-        // where the 7-bit code names the candidate (its entry in L.tab_idx).  The
-        // wave-wide max K names a best candidate.  Another lane holds the same value
-        // exactly when its key differs from K in the code bits alone, i.e. when
-        // (key ^ K) - 1 < 127: one compare and a branch on the lane mask.  Each pick
-        // is handed over as {x, y, z, seq} by every lane at once (the data are
-        // wave-uniform, so no lane has to be singled out), and K itself is noted:
-        // it holds the pick's value and, through the code, its index.
-        auto hand_over = [&](int c, uint32_t K) {
-            u32x4 s;
-            s.x = f2u(px); s.y = f2u(py); s.z = f2u(pz); s.w = (uint32_t)(npicked + c);
-            lds_write16(pk_off + c * 16, s);
-            L.pk_key[c] = K;
-        };
-        // The wave-wide max of the next keys with the hand-over of pick c written
-        // between its steps: a DPP step must wait two issue slots for the result of
-        // the one before, and the hand-over's independent moves and writes fill them.
-        auto max_and_hand_over = [&](uint32_t key, int c, uint32_t Kc) {
-            uint32_t v = key;
-            u32x4 s;
-            v = umax(v, dpp_or_zero<kDppRowShr1>(v));
-            s.x = f2u(px); s.y = f2u(py);
-            v = umax(v, dpp_or_zero<kDppRowShr2>(v));
-            s.z = f2u(pz); s.w = (uint32_t)(npicked + c);
-            v = umax(v, dpp_or_zero<kDppRowShr4>(v));
-            const uint32_t at = pk_off + c * 16;
-            v = umax(v, dpp_or_zero<kDppRowShr8>(v));
-            lds_write16(at, s);
-            v = umax(v, dpp_or_zero<kDppRowBcast15, 0xa>(v));
-            L.pk_key[c] = Kc;
-            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)v, 31);
-            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
-            return lo > hi ? lo : hi;
-        };
-        if (total <= kWave) {
-            // one candidate per lane: lane L takes position L, code = L
-            const bool h = lane < total;
-            const u32x4 r0 = L.cmp_a[lane];
-            uint32_t v0 = h ? r0.x : 0u;
-            const uint32_t i0 = h ? r0.y : kNoIndex;
-            const float x0 = h ? u2f(r0.z) : 0.f, y0 = h ? u2f(r0.w) : 0.f,
-                        z0 = h ? L.cmp_z[lane] : 0.f;
-            L.tab_idx[lane] = i0;
-#ifdef FFPS_PROFILE
-            const uint64_t lc0 = clock64();
-#endif
-            // the first pick of the round is never below the threshold
-            uint32_t d = __builtin_elementwise_sub_sat(v0, T);
-            uint32_t key = (d << 7) | (uint32_t)lane;
-            uint32_t K = wave_max_u32(key);
-            while (true) {
-                pl = (int)(K & 127u);
-                if (__builtin_expect(__builtin_amdgcn_ballot_w64(((key ^ K) - 1u) < 127u) != 0, 0)) {
-                    // several candidates share the best value: the lowest index wins
-                    const uint32_t imin = wave_min_u32(d == (K >> 7) ? i0 : 0xffffffffu);
-                    pl = first_lane(d == (K >> 7) && i0 == imin);
-                    K = (K & ~127u) | (uint32_t)pl;
-                }
-                px = readlane_f(x0, pl);
-                py = readlane_f(y0, pl);
-                pz = readlane_f(z0, pl);
-                const int c = cnt++;
-                if (cnt >= cap) {
-                    hand_over(c, K);
-                    break;
-                }
-                v0 = f2u(min_dist(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
-                d = __builtin_elementwise_sub_sat(v0, T);
-                key = (d << 7) | (uint32_t)lane;
-                K = max_and_hand_over(key, c, K);
-                if ((K >> 7) == 0) break;
+        // ---- order: every lane ranks its candidates (positions `lane` and
+        //      `lane + 64`) by counting the candidates that precede them ----
+        const int p1 = lane + kWave;
+        const bool h0 = lane < total, h1 = p1 < total;
+        const uint32_t q0 = h0 ? (uint32_t)lane : 0u, q1 = h1 ? (uint32_t)p1 : 0u;  // safe positions
+        u32x4 c0, c1;
+        u32x2 w0, w1;
+        uint32_t i0, i1;
+        lds_read_pair(c0, c1, w0, w1, i0, i1, cand_off + q0 * 16, cand_off + q1 * 16, key_off + q0 * 4,
+                      key_off + q1 * 4, idx_off + q0 * 4, idx_off + q1 * 4);
+        uint32_t o0 = h0 ? c0.w : 0u, o1 = h1 ? c1.w : 0u;  // values at the start of the round
+        bool ties = false;
+        // Candidates go to their places in the order: records {x, y, z, sequence
+        // number as a pick if no candidate ahead is passed over} (what the workers
+        // take), values and indices.  Every lane then takes candidates number `lane`
+        // (set 0) and `lane + 64` (set 1) of the order, and sees whether the
+        // candidate behind each of them has the same value.
+        auto place = [&](int r0, int r1) {
+            if (h0) {
+                c0.w = (uint32_t)(npicked + r0);
+                lds_write16(cand_off + r0 * 16, c0);
+                lds_write4(key_off + r0 * 4, o0);
+                lds_write4(idx_off + r0 * 4, i0);
             }
-#ifdef FFPS_PROFILE
-            if (prof) {
-                prof->loop[0] += (uint32_t)(clock64() - lc0);
-                prof->loop[1] += cnt;
+            if (h1) {
+                c1.w = (uint32_t)(npicked + r1);
+                lds_write16(cand_off + r1 * 16, c1);
+                lds_write4(key_off + r1 * 4, o1);
+                lds_write4(idx_off + r1 * 4, i1);
             }
-#endif
+            if (lane == 0) lds_write4(key_off + total * 4, 0u);  // behind the last value
+            lds_read_pair(c0, c1, w0, w1, i0, i1, cand_off + q0 * 16, cand_off + q1 * 16,
+                          key_off + q0 * 4, key_off + q1 * 4, idx_off + q0 * 4, idx_off + q1 * 4);
+            o0 = h0 ? w0.x : 0u;
+            o1 = h1 ? w1.x : 0u;
+            ties = __builtin_amdgcn_ballot_w64((h0 && w0.y == w0.x) || (h1 && w1.y == w1.x)) != 0;
+        };
+        // by (value descending, index ascending) on the full values: always right
+        auto order_exact = [&]() {
+            const uint64_t key0 = ((uint64_t)o0 << 32) | ~i0, key1 = ((uint64_t)o1 << 32) | ~i1;
+            int r0 = 0, r1 = 0;
+            for (int j = 0; j < total; ++j) {
+                const uint64_t kj = ((uint64_t)lds_read4(key_off + j * 4) << 32) | ~lds_read4(idx_off + j * 4);
+                r0 += kj > key0 ? 1 : 0;
+                r1 += kj > key1 ? 1 : 0;
+            }
+            place(r0, r1);
+        };
+        if (narrow) {
+            const uint32_t key0 = ((o0 - T) << 7) | (uint32_t)lane, key1 = ((o1 - T) << 7) | (uint32_t)p1;
+            int r0 = 0, r1 = 0;
+            for (int j = 0; j < total; j += 32) {
+                // thirty-two keys per step, read by all lanes from the same addresses (a broadcast)
+                u32x4 k[8];
+                lds_read128(k, key_off + j * 4);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    r0 += k[e].x > key0 ? 1 : 0; r0 += k[e].y > key0 ? 1 : 0;
+                    r0 += k[e].z > key0 ? 1 : 0; r0 += k[e].w > key0 ? 1 : 0;
+                }
+                if (total > kWave) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        r1 += k[e].x > key1 ? 1 : 0; r1 += k[e].y > key1 ? 1 : 0;
+                        r1 += k[e].z > key1 ? 1 : 0; r1 += k[e].w > key1 ? 1 : 0;
+                    }
+                }
+            }
+            place(r0, r1);
+            if (ties) order_exact();  // the values are in LDS in order now: equal neighbours are ties
         } else {
-            // two candidates per lane (positions L and L + 64), the lower index first,
-            // so that a lane whose two values tie puts forward the right one;
-            // code = 2 L + (0 for the first, 1 for the second)
-            const int p1 = lane + kWave;
-            const bool h1 = p1 < total;  // position L itself is always taken here
-            const u32x4 r0 = L.cmp_a[lane], r1 = L.cmp_a[p1];
-            uint32_t v0 = r0.x, v1 = h1 ? r1.x : 0u;
-            uint32_t i0 = r0.y, i1 = h1 ? r1.y : kNoIndex;
-            float x0 = u2f(r0.z), y0 = u2f(r0.w), z0 = L.cmp_z[lane];
-            float x1 = h1 ? u2f(r1.z) : 0.f, y1 = h1 ? u2f(r1.w) : 0.f, z1 = h1 ? L.cmp_z[p1] : 0.f;
-            if (i1 < i0) {
-                uint32_t tu;
-                float tf;
-                tu = v0; v0 = v1; v1 = tu;
-                tu = i0; i0 = i1; i1 = tu;
-                tf = x0; x0 = x1; x1 = tf;
-                tf = y0; y0 = y1; y1 = tf;
-                tf = z0; z0 = z1; z1 = tf;
-            }
-            L.tab_idx[2 * lane] = i0;
-            L.tab_idx[2 * lane + 1] = i1;
+            lds_write4(key_off + q0 * 4, c0.w);  // order_exact reads the values there
+            if (h1) lds_write4(key_off + p1 * 4, c1.w);
+            order_exact();
+        }
+        const float x0 = u2f(c0.x), y0 = u2f(c0.y), z0 = u2f(c0.z);
+        const float x1 = u2f(c1.x), y1 = u2f(c1.y), z1 = u2f(c1.z);
+        uint32_t v0 = o0, v1 = o1;  // current values
+        FFPS_SUB(3);
 #ifdef FFPS_PROFILE
-            const uint64_t lc0 = clock64();
+        const uint64_t lc0 = clock64();
 #endif
-            uint32_t bd, key;
-            float bx, by, bz;
-            bool sec;
-            auto keys_of_lane = [&]() {
-                const uint32_t d0 = __builtin_elementwise_sub_sat(v0, T);
-                const uint32_t d1 = __builtin_elementwise_sub_sat(v1, T);
-                sec = d1 > d0;  // strict: equal values put the lower index forward
-                bx = sec ? x1 : x0; by = sec ? y1 : y0; bz = sec ? z1 : z0;
-                bd = sec ? d1 : d0;
-                key = (bd << 7) | ((uint32_t)lane << 1) | (sec ? 1u : 0u);
-            };
-            keys_of_lane();
-            uint32_t K = wave_max_u32(key);  // the first pick is never below the threshold
+        // ---- replay, one set after the other ----
+        uint64_t gone0 = 0ull, gone1 = 0ull;  // candidates passed over
+        int ngone = 0;
+        bool stop = false;
+        // Candidates [base, base + n) of the order are lanes 0 .. n-1 of a set.
+        // Candidate base + li is pick number base + li - ngone of the round, so with
+        // `cap` picks allowed the set ends at lane cap + ngone - base.  Returns the
+        // number of candidates of the set that were dealt with.
+        auto run_set = [&](uint32_t &v, uint32_t o, float x, float y, float z, int base, int n,
+                           uint64_t &gone) {
+            int li = 0;
             while (true) {
-                pl = (int)((K >> 1) & 63u);
-                if (__builtin_expect(__builtin_amdgcn_ballot_w64(((key ^ K) - 1u) < 127u) != 0, 0)) {
-                    const uint32_t bidx = sec ? i1 : i0;
-                    const uint32_t imin = wave_min_u32(bd == (K >> 7) ? bidx : 0xffffffffu);
-                    pl = first_lane(bd == (K >> 7) && bidx == imin);
-                    K = (K & ~127u) | (uint32_t)readlane_i((int)(key & 127u), pl);
-                }
-                px = readlane_f(bx, pl);
-                py = readlane_f(by, pl);
-                pz = readlane_f(bz, pl);
-                const int c = cnt++;
-                if (cnt >= cap) {
-                    hand_over(c, K);
+                const int lend = n < cap + ngone - base ? n : cap + ngone - base;
+                if (li >= lend) break;
+                const int c = base + lane - ngone;  // this lane's candidate as a pick of the round
+                uint64_t bit = 1ull << li;
+                ordered_run(v, lane < lend ? o : 0xffffffffu, x, y, z, (uint32_t)(npicked + c),
+                            pk_off + (uint32_t)c * 16, bit, li);
+                if (li >= lend) break;
+                // candidate li has been lowered by a pick of this round
+                if ((uint32_t)readlane_i((int)v, li) > T) {
+                    stop = true;  // still a candidate, but maybe no longer the next one
                     break;
                 }
-                v0 = f2u(min_dist(u2f(v0), sqdist(x0, y0, z0, px, py, pz)));
-                v1 = f2u(min_dist(u2f(v1), sqdist(x1, y1, z1, px, py, pz)));
-                keys_of_lane();
-                K = max_and_hand_over(key, c, K);
-                if ((K >> 7) == 0) break;
+                // out of this round: the candidates behind it become picks one number earlier
+                gone |= 1ull << li;
+                ++ngone;
+                ++li;
             }
-#ifdef FFPS_PROFILE
-            if (prof) {
-                prof->loop[2] += (uint32_t)(clock64() - lc0);
-                prof->loop[3] += cnt;
+            return li;
+        };
+        const int nA = total < kWave ? total : kWave;
+        const int iA = run_set(v0, o0, x0, y0, z0, 0, nA, gone0);
+        int iB = 0;
+        if (!stop && iA == kWave && total > kWave && cap + ngone > kWave) {
+            // set 1 has not seen the picks of set 0 yet: apply them (the workers are
+            // busy with the same picks meanwhile)
+            const int done = kWave - ngone;
+            for (int c = 0; c < done; c += 2) {
+                u32x4 ra, rb;  // an odd count applies the last pick twice, which changes nothing
+                lds_read16x2(ra, rb, pk_off + c * 16, pk_off + (c + 1 < done ? c + 1 : c) * 16);
+                v1 = f2u(min_dist(u2f(v1), sqdist(x1, y1, z1, u2f(ra.x), u2f(ra.y), u2f(ra.z))));
+                v1 = f2u(min_dist(u2f(v1), sqdist(x1, y1, z1, u2f(rb.x), u2f(rb.y), u2f(rb.z))));
             }
-#endif
+            iB = run_set(v1, o1, x1, y1, z1, kWave, total - kWave, gone1);
         }
+        cnt = iA + iB - ngone;
+        // the candidates dealt with were picked unless passed over; the pick number
+        // of one of them is its place minus the candidates passed over before it
+        const int g0 = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(gone0 >> 32),
+                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)gone0, 0u));
+        const int g1 = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(gone1 >> 32),
+                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)gone1, 0u));
+        if (lane < iA && !((gone0 >> lane) & 1ull)) res.pc[0] = lane - g0;
+        if (lane < iB && !((gone1 >> lane) & 1ull)) res.pc[1] = p1 - __builtin_popcountll(gone0) - g1;
+        res.pi[0] = i0; res.pi[1] = i1;
+        res.pv[0] = o0; res.pv[1] = o1;
+#ifdef FFPS_PROFILE
+        if (prof) {
+            prof->loop[total <= kWave ? 0 : 2] += (uint32_t)(clock64() - lc0);
+            prof->loop[total <= kWave ? 1 : 3] += cnt;
+        }
+#endif
     } else {
-        // a single pick (best candidate not above the bound, or cap 1), or values
-        // spread too far above the threshold for the packed key: work on all
-        // candidates of every lane
+        // a single pick (best candidate not above the bound, or cap 1), or more
+        // than 128 candidates above every threshold tried: work on all candidates
+        // of every lane
         while (true) {
             uint32_t bv, bi;
             int bq;
@@ -570,28 +695,26 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 cv[q] = f2u(fminf(u2f(cv[q]), sqdist(cx[q], cy[q], cz[q], px, py, pz)));
         }
     }
-    RoundResult res;
     res.cnt = cnt;
-    res.by_key = packed;
-    res.T = T;
+    res.by_lane = ordered;
     return res;
 }
 
 __device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const RoundResult &r,
                                              int npicked, int32_t *idx_out, float *md_out) {
-    for (int c = lane; c < r.cnt; c += kWave) {
-        uint32_t idx, val;
-        if (r.by_key) {
-            // the key holds the pick's value above the threshold and the code of its candidate
-            const uint32_t K = L.pk_key[c];
-            idx = L.tab_idx[K & 127u];
-            val = (K >> 7) + r.T;
-        } else {
-            idx = L.pk_idx[c];
-            val = L.pk_val[c];
+    if (r.by_lane) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            if (r.pc[e] >= 0) {
+                idx_out[npicked + r.pc[e]] = (int32_t)r.pi[e];
+                if (md_out) md_out[npicked + r.pc[e]] = u2f(r.pv[e]);
+            }
         }
-        idx_out[npicked + c] = (int32_t)idx;
-        if (md_out) md_out[npicked + c] = u2f(val);
+        return;
+    }
+    for (int c = lane; c < r.cnt; c += kWave) {
+        idx_out[npicked + c] = (int32_t)L.pk_idx[c];
+        if (md_out) md_out[npicked + c] = u2f(L.pk_val[c]);
     }
 }
 
@@ -656,11 +779,28 @@ __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchang
     }
     FFPS_STAMP(prof, 3);
     if (gave_up) {
-        if (lane == 0) __hip_atomic_store(status, -5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        RoundResult failed;
+        // the first workgroup to give up notes what it was waiting for: status[2] =
+        // round, status[3] = lowest unit whose record had not arrived, status[4] = its own unit
+        int missing = 0x7fffffff;
+#pragma unroll
+        for (int q = kRPL - 1; q >= 0; --q) {
+            bool ok = true;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) ok = ok && chunk_ok(r[c][q], round, (uint32_t)c);
+            if (!ok && q * kWave + lane < U) missing = q * kWave + lane;
+        }
+        missing = (int)wave_min_u32((uint32_t)missing);
+        if (lane == 0) {
+            int expected = 0;
+            if (__hip_atomic_compare_exchange_strong(status, &expected, -5, __ATOMIC_RELAXED,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+                status[2] = (int)round;
+                status[3] = missing;
+                status[4] = unit0;
+            }
+        }
+        RoundResult failed = {};
         failed.cnt = -1;
-        failed.by_key = false;
-        failed.T = 0u;
         return failed;
     }
     // candidate c = T q + t of this lane: unit q*64 + lane, its t-th entry

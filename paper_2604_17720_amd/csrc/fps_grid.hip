@@ -7,10 +7,10 @@
 // indices over all workgroups, so an input that is already in farthest-point
 // order (a layer of a stage chain) yields as many picks per round as any other.
 // A workgroup is one COMMUNICATION wave (wave 0) plus NWK WORKER waves that own
-// the points.
-// Waves i and i+4 of a workgroup share a SIMD, so waves 4, 8 and 12 exit at
-// once: the communication wave, whose dependent chain sets the pace, then has
-// its SIMD to itself and the workers fill the other three.
+// the points.  Waves i and i+4 of a workgroup share a SIMD; with NWK + 1 = 4, 8
+// or 16 waves every SIMD carries the same number of waves, one of those of SIMD
+// 0 being the communication wave, whose replay costs about as much arithmetic
+// per pick as a worker wave with one or two points per lane.
 //
 // Workgroups meet once per ROUND (fps_exchange.h), and a round can deliver many
 // picks.  The workers apply the picks of a round to their points one by one,
@@ -57,12 +57,12 @@ struct GridArgs {  // pointers are those of the first cloud of the launch
 };
 
 // Number of waves a workgroup with NWK worker waves launches: wave 0
-// communicates, waves 4, 8, 12 exit at once, the rest work.
-__host__ __device__ constexpr int grid_waves(int nwk) { return nwk + nwk / 3; }
+// communicates, the others work.
+__host__ __device__ constexpr int grid_waves(int nwk) { return nwk + 1; }
 
 template <int NWK, int P>
 __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_in) {
-    static_assert(NWK % 3 == 0 && NWK >= 3 && NWK <= 12, "worker waves come in threes");
+    static_assert(NWK == 3 || NWK == 7 || NWK == 15, "four, eight or sixteen waves in all");
     __shared__ WaveTop wtop[NWK];
     __shared__ RoundLds L;
     // {batch id, picks emitted in total once that batch is complete}, one 8-byte word
@@ -83,7 +83,6 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
-    if (wave != 0 && (wave & 3) == 0) return;  // leaves the communication wave's SIMD to it
 
     // One pick handed from the communication wave to the workers is a single
     // 16-byte LDS word {x, y, z, seq}: written and read by one instruction each, so
@@ -97,7 +96,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         s.x = f2u(a.xyz[3 * (size_t)a.start + 0]);
         s.y = f2u(a.xyz[3 * (size_t)a.start + 1]);
         s.z = f2u(a.xyz[3 * (size_t)a.start + 2]);
-        for (int c = lane; c < kMaxPicksPerRound; c += kWave) {
+        for (int c = lane; c < kMaxPicksPerRound + 3; c += kWave) {
             s.w = c == 0 ? 0u : 0xffffffffu;
             lds_write16(pk_off + c * 16, s);
         }
@@ -116,7 +115,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
 
     if (wave != 0) {
         // =============================== worker ===============================
-        const int wk = wave - 1 - wave / 4;  // 0 .. NWK-1
+        const int wk = wave - 1;  // 0 .. NWK-1
         constexpr int NTW = NWK * kWave;
         const int t = wk * kWave + lane;      // worker thread number
         // element j of this lane is point (j * NTW + t) * G + w: ascending in j
@@ -134,29 +133,30 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         }
         int applied = 0;  // picks applied so far = sequence number of the next pick
         for (int batch = 0;; ++batch) {
-            // ---- 1a. take this batch's picks from LDS as they appear; the read of
-            //      the next slot is in flight while the current pick is applied ----
+            // ---- 1a. take this batch's picks from LDS as they appear, four slots per
+            //      read (the others are often there already) ----
             const int batch_base = applied;
-            u32x4 slot = lds_read16(pk_off);
             while (true) {
-                // every lane read the same slot: the sequence number is wave-uniform
-                if (__builtin_amdgcn_readfirstlane((int)slot.w) == applied) {
-                    const float lx = u2f(slot.x), ly = u2f(slot.y), lz = u2f(slot.z);
-                    ++applied;
-                    const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
-                    lds_issue16(slot, pk_off + pos * 16);
+                const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
+                u32x4 sl[4];
+                lds_read64(sl[0], sl[1], sl[2], sl[3], pk_off + pos * 16);
+                // every lane read the same slots: the sequence numbers are wave-uniform
+                if (__builtin_amdgcn_readfirstlane((int)sl[0].w) == applied) {
 #pragma unroll
-                    for (int j = 0; j < P; ++j)
-                        m[j] = fminf(m[j], sqdist(x[j], y[j], z[j], lx, ly, lz));
-                    lds_wait16(slot);
+                    for (int e = 0; e < 4; ++e) {
+                        if (__builtin_amdgcn_readfirstlane((int)sl[e].w) != applied) break;
+                        ++applied;
+                        const float lx = u2f(sl[e].x), ly = u2f(sl[e].y), lz = u2f(sl[e].z);
+#pragma unroll
+                        for (int j = 0; j < P; ++j)
+                            m[j] = min_dist(m[j], sqdist(x[j], y[j], z[j], lx, ly, lz));
+                    }
                 } else {
                     const u32x2 f = lds_read8(fin_off);
                     if (__builtin_amdgcn_readfirstlane((int)f.x) == batch &&
                         applied >= __builtin_amdgcn_readfirstlane((int)f.y))
                         break;
                     __builtin_amdgcn_s_sleep(1);
-                    const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
-                    slot = lds_read16(pk_off + pos * 16);
                 }
             }
             if (s_abort || applied >= a.M) break;
@@ -308,12 +308,14 @@ hipError_t launch_t(GridArgs &a, int num_wg, hipStream_t s) {
 }
 
 // Kernel shapes (worker waves, points per worker lane), ordered by capacity; a
-// workgroup's slice runs on the first shape that holds it.  One worker wave per
-// SIMD for small slices, two from 385 points per workgroup on.
-#define FFPS_GRID_SHAPES(X) \
-    X(3, 1) X(3, 2) X(6, 2) X(6, 3) X(6, 4) X(6, 5) X(6, 6) X(6, 8) X(12, 6) X(12, 8) X(12, 12) X(12, 16)
+// workgroup's slice runs on the first shape that holds it.  Among shapes of
+// similar capacity the one with fewer points per lane and more waves does less
+// arithmetic per pick on its busiest SIMD.
+#define FFPS_GRID_SHAPES(X)                                                                     \
+    X(3, 1) X(3, 2) X(7, 1) X(3, 3) X(7, 2) X(7, 3) X(7, 4) X(15, 2) X(7, 5) X(15, 3) X(15, 4) \
+    X(15, 5) X(15, 6) X(15, 8) X(15, 10) X(15, 13)
 
-constexpr int kMaxPointsPerWG = 12 * kWave * 16;
+constexpr int kMaxPointsPerWG = 12 * kWave * 16;  // 12288 <= 15 * 64 * 13
 
 // Worker waves of the shape that holds per_wg points (0 if none does).
 int shape_waves(int per_wg) {

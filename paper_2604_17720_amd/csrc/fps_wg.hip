@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
         s.x = f2u(a.xyz[3 * (size_t)a.start + 0]);
         s.y = f2u(a.xyz[3 * (size_t)a.start + 1]);
         s.z = f2u(a.xyz[3 * (size_t)a.start + 2]);
-        for (int c = lane; c < kMaxPicksPerRound; c += kWave) {
+        for (int c = lane; c < kMaxPicksPerRound + 3; c += kWave) {
             s.w = c == 0 ? 0u : 0xffffffffu;
             lds_write16(pk_off + c * 16, s);
         }
@@ -217,32 +217,30 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
         __syncthreads();  // pick slots and coordinates in place
         int applied = 0;  // picks applied so far = sequence number of the next pick
         for (int batch = 0;; ++batch) {
-            // ---- take this batch's picks from LDS as they appear; the read of the
-            //      next slot is in flight while the current pick is applied ----
+            // ---- take this batch's picks from LDS as they appear, four slots per read
+            //      (the others are often there already) ----
             const int batch_base = applied;
-            u32x4 slot = lds_read16(pk_off);
             while (true) {
-                // every lane read the same slot: the sequence number is wave-uniform
-                if (__builtin_amdgcn_readfirstlane((int)slot.w) == applied) {
-                    const float lx = u2f(slot.x), ly = u2f(slot.y), lz = u2f(slot.z);
-                    ++applied;
-                    const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
-                    lds_issue16(slot, pk_off + pos * 16);
+                const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
+                u32x4 sl[4];
+                lds_read64(sl[0], sl[1], sl[2], sl[3], pk_off + pos * 16);
+                // every lane read the same slots: the sequence numbers are wave-uniform
+                if (__builtin_amdgcn_readfirstlane((int)sl[0].w) == applied) {
 #pragma unroll
-                    for (int j = 0; j < P; ++j) {
-                        // distances are >= +0: the smaller bit pattern is the smaller value
-                        const uint32_t d = f2u(sqdist(x[j], y[j], z[j], lx, ly, lz));
-                        m[j] = u2f(d < f2u(m[j]) ? d : f2u(m[j]));
+                    for (int e = 0; e < 4; ++e) {
+                        if (__builtin_amdgcn_readfirstlane((int)sl[e].w) != applied) break;
+                        ++applied;
+                        const float lx = u2f(sl[e].x), ly = u2f(sl[e].y), lz = u2f(sl[e].z);
+#pragma unroll
+                        for (int j = 0; j < P; ++j)
+                            m[j] = min_dist(m[j], sqdist(x[j], y[j], z[j], lx, ly, lz));
                     }
-                    lds_wait16(slot);
                 } else {
                     const u32x2 f = lds_read8(fin_off);
                     if (__builtin_amdgcn_readfirstlane((int)f.x) == batch &&
                         applied >= __builtin_amdgcn_readfirstlane((int)f.y))
                         break;
                     __builtin_amdgcn_s_sleep(1);
-                    const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
-                    slot = lds_read16(pk_off + pos * 16);
                 }
             }
             if (applied >= a.M) break;
