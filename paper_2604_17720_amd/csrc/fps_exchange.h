@@ -276,9 +276,9 @@ struct RoundInput {
 
 // LDS used by the wave that runs exchange_round.
 struct RoundLds {
-    // picks of the round: {x, y, z, seq}; three spare slots that are never picks,
-    // so that readers may always read a slot and the three behind it
-    __attribute__((aligned(16))) u32x4 pk[kMaxPicksPerRound + 3];
+    // picks of the round: {x, y, z, seq}; spare slots that are never picks (they
+    // keep the seed point), so that readers may read a few slots past the last pick
+    __attribute__((aligned(16))) u32x4 pk[kMaxPicksPerRound + 8];
     uint32_t pk_idx[kMaxPicksPerRound];  // index of each pick of the round (general replay loop)
     uint32_t pk_val[kMaxPicksPerRound];  // and the value it was picked with
     // live candidates, first in compaction order, then in the order of the replay:
@@ -293,6 +293,7 @@ struct RoundProf {
     uint32_t acc[8];   // 100 MHz ticks per phase; [5], [6]: rounds of the ordered replay with up to 64 / more candidates; [7]: polls
     uint32_t loop[4];  // shader cycles and picks inside the ordered replay's pick loop, by the same split
     uint32_t sub[4];   // shader cycles of the replay set-up: bounds, counting, compaction, ordering
+    uint32_t ev[4];    // live candidates, candidates passed over, rounds ended by a lowered candidate, exact re-orderings
     uint64_t last;
 };
 #ifdef FFPS_PROFILE
@@ -312,27 +313,33 @@ struct RoundProf {
 
 // The inner loop of the ordered replay, for one set of candidates (lane L holds
 // candidate L of the set: current value v, coordinates x, y, z; `o` is the value
-// it had at the start of the round, or 0xffffffff for a lane at which the run
-// must end; `seq` is the sequence number the candidate has as a pick and `a_pk`
-// the address of the LDS slot it goes to, both per lane).  Starting at candidate
-// i, with `bit` = 1 << i, for as long as candidate i's value is unchanged (v ==
-// o in lane i): lane i alone writes its record {x, y, z, seq} to its slot for the
-// worker waves, its coordinates are read out of the lane, every lane's value is
-// lowered by the squared distance to it, and i steps on.  `bit` runs off the top
-// after lane 63, which ends the run as well.  Returns with i and `bit` at the
-// first candidate that was not handed over (bit 0: the set is used up).
-// 21 instructions per pick and nothing to wait for: LDS is only written.  The
-// registers named in the text are scratch of this block; distances are the
+// it had at the start of the round, or 0xffffffff for the lanes from `lim` on,
+// where the set ends; `seq` is the sequence number the candidate has as a pick
+// and `a_pk` the address of the LDS slot it goes to, both per lane).  Starting
+// at candidate i, with `bit` = 1 << i:
+//   - candidate i's value is unchanged (v == o in lane i): lane i alone writes
+//     its record {x, y, z, seq} to its slot for the worker waves, its
+//     coordinates are read out of the lane, every lane's value is lowered by
+//     the squared distance to it, and i steps on (21 instructions, nothing to
+//     wait for: LDS is only written);
+//   - it has been lowered to the threshold T or below: it is out of this round;
+//     its bit is noted in `gone`, the sequence numbers and slots of all lanes
+//     move down by one, and i steps on.  With `soft` set the block returns here
+//     instead (the caller then moves the end of the set, which depends on the
+//     number of candidates passed over when the picks left to do are few);
+//   - it has been lowered but is still above T, or i has reached `lim`: return.
+// The registers named in the text are scratch of this block; distances are the
 // individually rounded operations of sqdist; a lane read into a scalar register
 // needs two instructions before a vector instruction may use it, which the
 // order of the reads provides.
 __device__ __forceinline__ void ordered_run(uint32_t &v, uint32_t o, float x, float y, float z,
-                                            uint32_t seq, uint32_t a_pk, uint64_t &bit, int &i) {
+                                            uint32_t seq, uint32_t a_pk, uint64_t &bit, int &i,
+                                            uint64_t &gone, uint32_t T, int lim, int soft) {
     uint32_t sx, sy, sz;
-#define FFPS_STEP(EXIT)                                   \
+#define FFPS_STEP                                          \
     "v_cmp_eq_u32 vcc, %[v], %[o]\n\t"                     \
     "s_and_b64 vcc, vcc, %[bit]\n\t"                       \
-    "s_cbranch_scc0 " EXIT "\n\t"                          \
+    "s_cbranch_scc0 7f\n\t"                                \
     "s_mov_b64 exec, vcc\n\t"                              \
     "ds_write_b128 %[ap], v[108:111]\n\t"                  \
     "s_mov_b64 exec, -1\n\t"                               \
@@ -356,12 +363,29 @@ __device__ __forceinline__ void ordered_run(uint32_t &v, uint32_t o, float x, fl
         "v_mov_b32 v110, %[z]\n\t"
         "v_mov_b32 v111, %[seq]\n\t"
         "1:\n\t"
-        FFPS_STEP("9f")
-        FFPS_STEP("9f")
+        FFPS_STEP
+        FFPS_STEP
+        "s_branch 1b\n\t"
+        "7:\n\t"
+        "s_cmp_ge_i32 %[i], %[lim]\n\t"
+        "s_cbranch_scc1 9f\n\t"
+        "s_cmp_lg_u32 %[soft], 0\n\t"
+        "s_cbranch_scc1 9f\n\t"
+        "v_readlane_b32 %[sx], %[v], %[i]\n\t"
+        "s_nop 1\n\t"
+        "s_cmp_gt_u32 %[sx], %[T]\n\t"
+        "s_cbranch_scc1 9f\n\t"
+        "s_or_b64 %[gone], %[gone], %[bit]\n\t"
+        "v_subrev_u32 v111, 1, v111\n\t"
+        "v_subrev_u32 %[ap], 16, %[ap]\n\t"
+        "s_lshl_b64 %[bit], %[bit], 1\n\t"
+        "s_add_i32 %[i], %[i], 1\n\t"
         "s_branch 1b\n\t"
         "9:\n\t"
-        : [v] "+v"(v), [bit] "+s"(bit), [i] "+s"(i), [sx] "=&s"(sx), [sy] "=&s"(sy), [sz] "=&s"(sz)
-        : [o] "v"(o), [x] "v"(x), [y] "v"(y), [z] "v"(z), [seq] "v"(seq), [ap] "v"(a_pk)
+        : [v] "+v"(v), [bit] "+s"(bit), [i] "+s"(i), [gone] "+s"(gone), [ap] "+v"(a_pk), [sx] "=&s"(sx),
+          [sy] "=&s"(sy), [sz] "=&s"(sz)
+        : [o] "v"(o), [x] "v"(x), [y] "v"(y), [z] "v"(z), [seq] "v"(seq), [T] "s"(T), [lim] "s"(lim),
+          [soft] "s"(soft)
         : "memory", "vcc", "scc", "v108", "v109", "v110", "v111", "v112", "v113", "v114");
 #undef FFPS_STEP
 }
@@ -624,12 +648,20 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                            uint64_t &gone) {
             int li = 0;
             while (true) {
-                const int lend = n < cap + ngone - base ? n : cap + ngone - base;
+                // the end of the set moves with the candidates passed over only when
+                // fewer picks are left to do than the set has candidates
+                const bool soft = cap - base < n;
+                const int lend = soft ? (n < cap + ngone - base ? n : cap + ngone - base) : n;
                 if (li >= lend) break;
                 const int c = base + lane - ngone;  // this lane's candidate as a pick of the round
                 uint64_t bit = 1ull << li;
+                const uint64_t gone_before = gone;
                 ordered_run(v, lane < lend ? o : 0xffffffffu, x, y, z, (uint32_t)(npicked + c),
-                            pk_off + (uint32_t)c * 16, bit, li);
+                            pk_off + (uint32_t)c * 16, bit, li, gone,
+                            (uint32_t)__builtin_amdgcn_readfirstlane((int)T),
+                            __builtin_amdgcn_readfirstlane(lend),
+                            __builtin_amdgcn_readfirstlane(soft ? 1 : 0));
+                ngone += __builtin_popcountll(gone ^ gone_before);
                 if (li >= lend) break;
                 // candidate li has been lowered by a pick of this round
                 if ((uint32_t)readlane_i((int)v, li) > T) {
@@ -649,16 +681,27 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
         if (!stop && iA == kWave && total > kWave && cap + ngone > kWave) {
             // set 1 has not seen the picks of set 0 yet: apply them (the workers are
             // busy with the same picks meanwhile)
+            // Eight slots per LDS read.  Slots behind the picks of this round hold
+            // picks of earlier rounds (or the seed point), which every value already
+            // reflects, so applying those again changes nothing.
             const int done = kWave - ngone;
-            for (int c = 0; c < done; c += 2) {
-                u32x4 ra, rb;  // an odd count applies the last pick twice, which changes nothing
-                lds_read16x2(ra, rb, pk_off + c * 16, pk_off + (c + 1 < done ? c + 1 : c) * 16);
-                v1 = f2u(min_dist(u2f(v1), sqdist(x1, y1, z1, u2f(ra.x), u2f(ra.y), u2f(ra.z))));
-                v1 = f2u(min_dist(u2f(v1), sqdist(x1, y1, z1, u2f(rb.x), u2f(rb.y), u2f(rb.z))));
+            for (int c = 0; c < done; c += 8) {
+                u32x4 r[8];
+                lds_read128(r, pk_off + c * 16);
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    v1 = f2u(min_dist(u2f(v1), sqdist(x1, y1, z1, u2f(r[e].x), u2f(r[e].y), u2f(r[e].z))));
             }
             iB = run_set(v1, o1, x1, y1, z1, kWave, total - kWave, gone1);
         }
         cnt = iA + iB - ngone;
+#ifdef FFPS_PROFILE
+        if (prof) {
+            prof->ev[0] += (uint32_t)total;
+            prof->ev[1] += (uint32_t)ngone;
+            prof->ev[2] += stop ? 1u : 0u;
+        }
+#endif
         // the candidates dealt with were picked unless passed over; the pick number
         // of one of them is its place minus the candidates passed over before it
         const int g0 = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(gone0 >> 32),

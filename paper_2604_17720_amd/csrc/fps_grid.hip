@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         s.x = f2u(a.xyz[3 * (size_t)a.start + 0]);
         s.y = f2u(a.xyz[3 * (size_t)a.start + 1]);
         s.z = f2u(a.xyz[3 * (size_t)a.start + 2]);
-        for (int c = lane; c < kMaxPicksPerRound + 3; c += kWave) {
+        for (int c = lane; c < kMaxPicksPerRound + 8; c += kWave) {
             s.w = c == 0 ? 0u : 0xffffffffu;
             lds_write16(pk_off + c * 16, s);
         }
@@ -294,6 +294,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         for (int i = 0; i < 8; ++i) a.status[8 + i] = (int)prof_store.acc[i];
         for (int i = 0; i < 4; ++i) a.status[20 + i] = (int)prof_store.loop[i];
         for (int i = 0; i < 4; ++i) a.status[24 + i] = (int)prof_store.sub[i];
+        for (int i = 0; i < 4; ++i) a.status[28 + i] = (int)prof_store.ev[i];
         a.status[16] = (int)(wall_clock64() - prof_w0);       // 10 ns units
         a.status[17] = (int)((clock64() - prof_c0) >> 4);     // shader cycles / 16
 #endif

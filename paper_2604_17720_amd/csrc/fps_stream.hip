@@ -50,13 +50,19 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
     const int hi = min(a.N, lo + a.chunk);
     const uint32_t pk_off = lds_offset(L.pk);
 
-    if (tid == 0) {
+    if (tid < kWave) {
+        // every pick slot starts as the seed point: the replay may read slots behind
+        // the picks of a round, and a point picked earlier changes nothing
         u32x4 s;
         s.x = f2u(a.xyz[3 * (size_t)a.start + 0]);
         s.y = f2u(a.xyz[3 * (size_t)a.start + 1]);
         s.z = f2u(a.xyz[3 * (size_t)a.start + 2]);
-        s.w = 0u;
-        lds_write16(pk_off, s);
+        for (int c = tid; c < kMaxPicksPerRound + 8; c += kWave) {
+            s.w = c == 0 ? 0u : 0xffffffffu;
+            lds_write16(pk_off + c * 16, s);
+        }
+    }
+    if (tid == 0) {
         s_cnt = 1;
         s_abort = 0;
         if (w == 0) {

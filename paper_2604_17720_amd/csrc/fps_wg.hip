@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
         s.x = f2u(a.xyz[3 * (size_t)a.start + 0]);
         s.y = f2u(a.xyz[3 * (size_t)a.start + 1]);
         s.z = f2u(a.xyz[3 * (size_t)a.start + 2]);
-        for (int c = lane; c < kMaxPicksPerRound + 3; c += kWave) {
+        for (int c = lane; c < kMaxPicksPerRound + 8; c += kWave) {
             s.w = c == 0 ? 0u : 0xffffffffu;
             lds_write16(pk_off + c * 16, s);
         }

@@ -74,6 +74,8 @@ def _phases(args) -> None:
         if st[21] + st[23] > 0:
             print(f"- pick loop: {st[20] / max(st[21], 1):.0f} cycles per pick over {st[21]} picks with one "
                   f"candidate per lane, {st[22] / max(st[23], 1):.0f} over {st[23]} picks with two")
+        print(f"- per round: {st[28] / r:.1f} live candidates, {st[29] / r:.1f} passed over, "
+              f"{st[30] / r:.2f} rounds ended early by a lowered candidate")
         print(f"- rounds by path: one candidate per lane {st[13]}, two {st[14]}, general {r - st[13] - st[14]}")
         print(f"- kernel: {st[16] * 0.01:.1f} us wall, {st[17] * 16 / (st[16] * 10.0):.3f} GHz shader clock\n")
 
