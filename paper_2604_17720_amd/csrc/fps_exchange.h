@@ -152,6 +152,14 @@ __device__ __forceinline__ u32x4 lds_read16(uint32_t off) {
     return r;
 }
 
+// Two dwords, `d0` and `d1` dwords behind `off` (both below 256), complete on return.
+template <int D0, int D1>
+__device__ __forceinline__ u32x2 lds_read2(uint32_t off) {
+    u32x2 r;
+    asm volatile("ds_read2_b32 %0, %1 offset0:%2 offset1:%3\n\ts_waitcnt lgkmcnt(0)"
+                 : "=v"(r) : "v"(off), "n"(D0), "n"(D1) : "memory");
+    return r;
+}
 // Two 16-byte reads in flight together, complete on return.
 __device__ __forceinline__ void lds_read16x2(u32x4 &a, u32x4 &b, uint32_t off_a, uint32_t off_b) {
     asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
@@ -321,7 +329,9 @@ struct RoundProf {
 //     its record {x, y, z, seq} to its slot for the worker waves, its
 //     coordinates are read out of the lane, every lane's value is lowered by
 //     the squared distance to it, and i steps on (21 instructions, nothing to
-//     wait for: LDS is only written);
+//     wait for: LDS is only written).  The distances are worked out before the
+//     branch on the comparison, whose way from the vector to the scalar unit is
+//     long; a candidate that turns out lowered has cost eight wasted operations;
 //   - it has been lowered to the threshold T or below: it is out of this round;
 //     its bit is noted in `gone`, the sequence numbers and slots of all lanes
 //     move down by one, and i steps on.  With `soft` set the block returns here
@@ -337,15 +347,10 @@ __device__ __forceinline__ void ordered_run(uint32_t &v, uint32_t o, float x, fl
                                             uint64_t &gone, uint32_t T, int lim, int soft) {
     uint32_t sx, sy, sz;
 #define FFPS_STEP                                          \
-    "v_cmp_eq_u32 vcc, %[v], %[o]\n\t"                     \
-    "s_and_b64 vcc, vcc, %[bit]\n\t"                       \
-    "s_cbranch_scc0 7f\n\t"                                \
-    "s_mov_b64 exec, vcc\n\t"                              \
-    "ds_write_b128 %[ap], v[108:111]\n\t"                  \
-    "s_mov_b64 exec, -1\n\t"                               \
     "v_readlane_b32 %[sx], %[x], %[i]\n\t"                 \
     "v_readlane_b32 %[sy], %[y], %[i]\n\t"                 \
     "v_readlane_b32 %[sz], %[z], %[i]\n\t"                 \
+    "v_cmp_eq_u32 vcc, %[v], %[o]\n\t"                     \
     "v_subrev_f32 v112, %[sx], %[x]\n\t"                   \
     "v_subrev_f32 v113, %[sy], %[y]\n\t"                   \
     "v_subrev_f32 v114, %[sz], %[z]\n\t"                   \
@@ -354,6 +359,11 @@ __device__ __forceinline__ void ordered_run(uint32_t &v, uint32_t o, float x, fl
     "v_mul_f32 v114, v114, v114\n\t"                       \
     "v_add_f32 v112, v112, v113\n\t"                       \
     "v_add_f32 v112, v112, v114\n\t"                       \
+    "s_and_b64 vcc, vcc, %[bit]\n\t"                       \
+    "s_cbranch_scc0 7f\n\t"                                \
+    "s_mov_b64 exec, vcc\n\t"                              \
+    "ds_write_b128 %[ap], v[108:111]\n\t"                  \
+    "s_mov_b64 exec, -1\n\t"                               \
     "v_min_f32 %[v], %[v], v112\n\t"                       \
     "s_lshl_b64 %[bit], %[bit], 1\n\t"                     \
     "s_add_i32 %[i], %[i], 1\n\t"

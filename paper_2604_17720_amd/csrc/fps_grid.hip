@@ -213,6 +213,8 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
     }
 
     // ========================== communication wave ==========================
+    // it shares its SIMD with worker waves and sets the pace: it goes first
+    __builtin_amdgcn_s_setprio(3);
     int npicked = 1;
     uint32_t round = 0;
     RoundProf *prof = nullptr;
