@@ -112,7 +112,7 @@ int ffps_exact(const float *d_xyz, int B, int N, int M, int start_idx, int varia
  * ffps_exact for callers that cannot allocate device memory (code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): takes
  * no workspace and allocates nothing.  What the kernels need besides inputs and
- * outputs (the status block and the exchange areas of one launch, 8 MiB + 256
+ * outputs (the status block and the exchange areas of one launch, 12 MiB + 256
  * bytes) lives in an array inside the library's device image; every GPU the
  * library runs on holds its copy until the process ends.
  *   arguments   as ffps_exact, without d_ws / ws_bytes

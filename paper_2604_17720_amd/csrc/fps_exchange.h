@@ -31,6 +31,9 @@ constexpr int kMaxUnits = kMaxGridWG;     // reporting units of a cloud
 constexpr int kRPL = kMaxUnits / kWave;   // unit records per lane of the gathering wave
 constexpr int kSpinLimit = 1 << 19;
 constexpr uint32_t kNoIndex = 0x7fffffffu;  // index of a candidate that does not exist
+constexpr int kSets = 3;                    // the ordered replay takes up to kSets * 64 live candidates
+constexpr int kMaxLive = kSets * kWave;
+static_assert(kMaxPicksPerRound <= kMaxLive && kMaxLive <= 256, "a round picks live candidates only");
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -183,17 +186,20 @@ __device__ __forceinline__ void lds_read128(u32x4 (&r)[8], uint32_t off) {
                    "=&v"(r[6]), "=&v"(r[7])
                  : "v"(off) : "memory");
 }
-// The records of two candidates, their values (each with the value that follows
-// it in the array) and their indices, with all reads in flight together.
-__device__ __forceinline__ void lds_read_pair(u32x4 &c0, u32x4 &c1, u32x2 &v0, u32x2 &v1, uint32_t &i0,
-                                              uint32_t &i1, uint32_t a_c0, uint32_t a_c1, uint32_t a_v0,
-                                              uint32_t a_v1, uint32_t a_i0, uint32_t a_i1) {
-    asm volatile("ds_read_b128 %0, %6\n\tds_read_b128 %1, %7\n\t"
-                 "ds_read2_b32 %2, %8 offset1:1\n\tds_read2_b32 %3, %9 offset1:1\n\t"
-                 "ds_read_b32 %4, %10\n\tds_read_b32 %5, %11\n\t"
+// The records of three candidates, their values (each with the value that
+// follows it in the array) and their indices, with all reads in flight together.
+__device__ __forceinline__ void lds_read_own(u32x4 (&c)[3], u32x2 (&w)[3], uint32_t (&i)[3],
+                                             const uint32_t (&a_c)[3], const uint32_t (&a_w)[3],
+                                             const uint32_t (&a_i)[3]) {
+    asm volatile("ds_read_b128 %0, %9\n\tds_read_b128 %1, %10\n\tds_read_b128 %2, %11\n\t"
+                 "ds_read2_b32 %3, %12 offset1:1\n\tds_read2_b32 %4, %13 offset1:1\n\t"
+                 "ds_read2_b32 %5, %14 offset1:1\n\t"
+                 "ds_read_b32 %6, %15\n\tds_read_b32 %7, %16\n\tds_read_b32 %8, %17\n\t"
                  "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(c0), "=&v"(c1), "=&v"(v0), "=&v"(v1), "=&v"(i0), "=&v"(i1)
-                 : "v"(a_c0), "v"(a_c1), "v"(a_v0), "v"(a_v1), "v"(a_i0), "v"(a_i1)
+                 : "=&v"(c[0]), "=&v"(c[1]), "=&v"(c[2]), "=&v"(w[0]), "=&v"(w[1]), "=&v"(w[2]),
+                   "=&v"(i[0]), "=&v"(i[1]), "=&v"(i[2])
+                 : "v"(a_c[0]), "v"(a_c[1]), "v"(a_c[2]), "v"(a_w[0]), "v"(a_w[1]), "v"(a_w[2]),
+                   "v"(a_i[0]), "v"(a_i[1]), "v"(a_i[2])
                  : "memory");
 }
 __device__ __forceinline__ void lds_write4(uint32_t off, uint32_t v) {
@@ -289,11 +295,16 @@ struct RoundLds {
     __attribute__((aligned(16))) u32x4 pk[kMaxPicksPerRound + 8];
     uint32_t pk_idx[kMaxPicksPerRound];  // index of each pick of the round (general replay loop)
     uint32_t pk_val[kMaxPicksPerRound];  // and the value it was picked with
-    // live candidates, first in compaction order, then in the order of the replay:
-    __attribute__((aligned(16))) u32x4 cand[2 * kWave + 3];  // {x, y, z, value; later sequence number}; spare entries for reads ahead
-    __attribute__((aligned(16))) uint32_t keyw[2 * kWave + 32];  // 32-bit sort keys, zero-padded; later the values in order
-    // (entries cand[130], keyw[130], idxw[130] take what the compaction discards)
-    uint32_t idxw[2 * kWave + 3];                                // point indices
+    // live candidates, first in compaction order, then in the order of the replay;
+    // behind each array 64 entries, one per lane, take what the compaction discards
+    // (one common entry would make every such write a 64-way bank conflict)
+    __attribute__((aligned(16))) u32x4 cand[kMaxLive + 4 + kWave];  // {x, y, z, value; later sequence number}
+    __attribute__((aligned(16))) uint32_t keyw[kMaxLive + 32 + kWave];  // 32-bit sort keys, zero-padded; later the values in order
+    uint32_t idxw[kMaxLive + 4 + kWave];                                // point indices
+    // ranking by the whole workgroup: how many keys there are to rank (0: none this
+    // round) and the ranks, which the waves add up
+    uint32_t team_total;
+    uint32_t rank[kMaxLive];
 };
 
 // Counters of a profiling build (workgroup 0 only).
@@ -302,6 +313,7 @@ struct RoundProf {
     uint32_t loop[4];  // shader cycles and picks inside the ordered replay's pick loop, by the same split
     uint32_t sub[4];   // shader cycles of the replay set-up: bounds, counting, compaction, ordering
     uint32_t ev[4];    // live candidates, candidates passed over, rounds ended by a lowered candidate, exact re-orderings
+    uint32_t ord[6];   // shader cycles inside the ordering: own load, first barrier, ranking share, second barrier, placing, rest
     uint64_t last;
 };
 #ifdef FFPS_PROFILE
@@ -318,6 +330,85 @@ struct RoundProf {
     do {                 \
     } while (0)
 #endif
+
+// Workgroup barrier for LDS traffic issued by the assembly helpers of this file,
+// which the compiler does not know about and therefore does not wait for.
+__device__ __forceinline__ void team_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
+    __syncthreads();
+}
+
+// Nine words from nine addresses per lane, one wait.
+__device__ __forceinline__ void lds_read4x9(uint32_t (&r)[9], const uint32_t (&a)[9]) {
+    asm volatile("ds_read_b32 %0, %9\n\tds_read_b32 %1, %10\n\tds_read_b32 %2, %11\n\t"
+                 "ds_read_b32 %3, %12\n\tds_read_b32 %4, %13\n\tds_read_b32 %5, %14\n\t"
+                 "ds_read_b32 %6, %15\n\tds_read_b32 %7, %16\n\tds_read_b32 %8, %17\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]),
+                   "=&v"(r[7]), "=&v"(r[8])
+                 : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(a[8])
+                 : "memory");
+}
+
+// Ranking of the live candidates by all W waves of a workgroup (the wave that
+// replays and the worker waves, which have nothing else to do at that point).
+// L.keyw[0 .. total) holds the unique 32-bit sort keys, zero-padded behind the
+// last one; the rank of a candidate is the number of keys above its own.  Wave
+// number wv counts, for the candidates lane, lane + 64, ... , the keys of its
+// share [wv * chunk, (wv + 1) * chunk) that are above theirs and adds the
+// counts to L.rank, which starts at zero.  Called by every wave between two
+// workgroup barriers: the keys are in place before the first, the ranks are
+// complete after the second.
+__device__ __forceinline__ void team_rank(RoundLds &L, int lane, int wv_in, int W) {
+    const int total = __builtin_amdgcn_readfirstlane((int)lds_read4(lds_offset(&L.team_total)));
+    const int wv = __builtin_amdgcn_readfirstlane(wv_in);
+    if (total == 0) return;
+    const uint32_t key_off = lds_offset(L.keyw), rank_off = lds_offset(L.rank);
+    const int nsets = (total + kWave - 1) / kWave;
+    const int chunk = ((total + W - 1) / W + 3) & ~3;  // keys per wave, a multiple of four
+    const int j0 = wv * chunk;
+    if (j0 >= total) return;
+    const int j1 = j0 + chunk < total ? j0 + chunk : total;
+    // own keys (a lane without a candidate in set s reads padding or a key of
+    // another set, and its count goes nowhere) and the first sixteen keys of the
+    // share in one go
+    static_assert(kSets == 3, "three own keys are read");
+    uint32_t key[kSets];
+    int r[kSets] = {};
+    u32x4 ka, kb, kc, kd;
+    asm volatile("ds_read_b32 %0, %7\n\tds_read_b32 %1, %7 offset:256\n\tds_read_b32 %2, %7 offset:512\n\t"
+                 "ds_read_b128 %3, %8\n\tds_read_b128 %4, %8 offset:16\n\t"
+                 "ds_read_b128 %5, %8 offset:32\n\tds_read_b128 %6, %8 offset:48\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(key[0]), "=&v"(key[1]), "=&v"(key[2]), "=&v"(ka), "=&v"(kb), "=&v"(kc), "=&v"(kd)
+                 : "v"(key_off + (uint32_t)lane * 4), "v"(key_off + (uint32_t)j0 * 4)
+                 : "memory");
+    for (int j = j0; j < j1; j += 16) {
+        // sixteen keys per step (those behind the wave's share or behind the last
+        // key are skipped or zero), read by all lanes from the same addresses
+        if (j > j0) lds_read64(ka, kb, kc, kd, key_off + j * 4);
+        const uint32_t kk[16] = {ka.x, ka.y, ka.z, ka.w, kb.x, kb.y, kb.z, kb.w,
+                                 kc.x, kc.y, kc.z, kc.w, kd.x, kd.y, kd.z, kd.w};
+#pragma unroll
+        for (int g = 0; g < 16; g += 4) {
+            if (j + g < j1) {  // shares are multiples of four keys; the last one ends in zeros
+#pragma unroll
+                for (int s = 0; s < kSets; ++s) {
+                    if (s < nsets) {
+#pragma unroll
+                        for (int e = g; e < g + 4; ++e) r[s] += kk[e] > key[s] ? 1 : 0;
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < kSets; ++s) {
+        if (s < nsets && lane + s * kWave < total)
+            asm volatile("ds_add_u32 %0, %1" : : "v"(rank_off + (uint32_t)(lane + s * kWave) * 4),
+                         "v"((uint32_t)r[s]) : "memory");
+    }
+}
 
 // The inner loop of the ordered replay, for one set of candidates (lane L holds
 // candidate L of the set: current value v, coordinates x, y, z; `o` is the value
@@ -367,7 +458,13 @@ __device__ __forceinline__ void ordered_run(uint32_t &v, uint32_t o, float x, fl
     "v_min_f32 %[v], %[v], v112\n\t"                       \
     "s_lshl_b64 %[bit], %[bit], 1\n\t"                     \
     "s_add_i32 %[i], %[i], 1\n\t"
+    // The compiler does not hold back a block that overwrites a register named
+    // in its clobber list while a load into that register is still in flight (it
+    // reloads values it keeps in v108 .. v114 after the block, and the block may
+    // be entered again before such a reload has landed): the block waits for all
+    // outstanding loads itself before it touches those registers.
     asm volatile(
+        "s_waitcnt vmcnt(0) lgkmcnt(0)\n\t"
         "v_mov_b32 v108, %[x]\n\t"
         "v_mov_b32 v109, %[y]\n\t"
         "v_mov_b32 v110, %[z]\n\t"
@@ -412,10 +509,10 @@ __device__ __forceinline__ void ordered_run(uint32_t &v, uint32_t o, float x, fl
 struct RoundResult {
     int cnt;        // picks of the round, or -1 when the round failed
     bool by_lane;   // picks noted in the lanes (below) rather than in L.pk_idx / L.pk_val
-    // by_lane: what this lane's two candidates of the ordered replay became: pick
+    // by_lane: what this lane's candidates of the ordered replay became: pick
     // number within the round (-1: not picked), point index, value when picked
-    int pc[2];
-    uint32_t pi[2], pv[2];
+    int pc[kSets];
+    uint32_t pi[kSets], pv[kSets];
 };
 
 // Writes index (and value) of the picks of a round to the outputs; run by the
@@ -423,11 +520,15 @@ struct RoundResult {
 __device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const RoundResult &r,
                                              int npicked, int32_t *idx_out, float *md_out);
 
-template <int KC>
+// With TEAM the other waves of the workgroup take part in the ranking: they
+// wait at a workgroup barrier after handing in their reports, call team_rank
+// and pass a second barrier, every round; this function passes the same two
+// barriers exactly once, whatever path the round takes.
+template <int KC, bool TEAM = false>
 __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint32_t (&cv)[KC],
                                             uint32_t (&ci)[KC], float (&cx)[KC], float (&cy)[KC],
                                             float (&cz)[KC], uint32_t lb, int npicked, int cap,
-                                            RoundProf *prof) {
+                                            RoundProf *prof, int team_waves = 1) {
     const uint32_t pk_off = lds_offset(L.pk);
 #ifdef FFPS_PROFILE
     uint64_t sc = clock64();
@@ -441,6 +542,21 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
     } while (0)
 #else
 #define FFPS_SUB(i) \
+    do {            \
+    } while (0)
+#endif
+#ifdef FFPS_PROFILE
+    uint64_t oc = 0;
+#define FFPS_ORD(i)                              \
+    do {                                         \
+        if (prof) {                              \
+            uint64_t n_ = clock64();             \
+            prof->ord[i] += (uint32_t)(n_ - oc); \
+            oc = n_;                             \
+        }                                        \
+    } while (0)
+#else
+#define FFPS_ORD(i) \
     do {            \
     } while (0)
 #endif
@@ -478,8 +594,8 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
     // when the best candidate is above it the first pick is one of them too:
     // compact them (in any order).  Any threshold T >= Bound serves as well (the
     // round then ends when the best candidate is no longer above T), so when more
-    // than 128 candidates are above the bound T is raised to the largest
-    // third-best candidate value of any lane, which leaves at most two per lane.
+    // than kMaxLive candidates are above the bound T is raised to the largest
+    // value that is number kSets + 1 in its lane, which leaves at most kSets per lane.
     uint32_t T = Bound;
     int total = 0, before = 0;
     FFPS_SUB(0);
@@ -502,20 +618,21 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             }
         };
         count_live();
-        if (total > 2 * kWave) {
-            uint32_t t1 = 0u, t2 = 0u, t3 = 0u;
+        if (total > kMaxLive) {
+            // the largest value that is only number kSets + 1 in its lane
+            uint32_t t[kSets + 1] = {};
 #pragma unroll
             for (int q = 0; q < KC; ++q) {
                 const uint32_t v = cv[q];
-                t3 = umax(t3, v < t2 ? v : t2);
-                t2 = umax(t2, v < t1 ? v : t1);
-                t1 = umax(t1, v);
+#pragma unroll
+                for (int r = kSets; r >= 1; --r) t[r] = umax(t[r], v < t[r - 1] ? v : t[r - 1]);
+                t[0] = umax(t[0], v);
             }
-            T = umax(Bound, wave_max_u32(t3));
+            T = umax(Bound, wave_max_u32(t[kSets]));
             count_live();
         }
     }
-    // With at most 128 live candidates the replay needs no argmax per pick.  Put
+    // With at most kMaxLive live candidates the replay needs no argmax per pick.  Put
     // the candidates in the order (value descending, index ascending).  The first
     // one is the next pick.  Picking a point can only lower other values, so the
     // next candidate in that order is the following pick as long as its own value
@@ -527,135 +644,226 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
     // may now belong further back in the order, and the round ends before it
     // (the next round sees it with its new value).  Per pick this costs the
     // distance update of the candidates and one comparison.
-    const bool ordered = total >= 1 && total <= 2 * kWave;
+    const bool ordered = total >= 1 && total <= kMaxLive;
     FFPS_SUB(1);
 #ifdef FFPS_PROFILE
     if (prof && ordered) prof->acc[total <= kWave ? 5 : 6] += 1;
 #endif
     RoundResult res;
-    res.pc[0] = res.pc[1] = -1;
-    res.pi[0] = res.pi[1] = kNoIndex;
-    res.pv[0] = res.pv[1] = 0u;
+#pragma unroll
+    for (int s = 0; s < kSets; ++s) {
+        res.pc[s] = -1;
+        res.pi[s] = kNoIndex;
+        res.pv[s] = 0u;
+    }
     if (ordered) {
         const uint32_t cand_off = lds_offset(L.cand), key_off = lds_offset(L.keyw),
                        idx_off = lds_offset(L.idxw);
         // 32-bit sort key of a live candidate: its value above the threshold and its
-        // compaction position, (value - T) << 7 | position, which orders by value
+        // compaction position, (value - T) << 8 | position, which orders by value
         // and is unique.  Candidates of equal value come out in position order
         // rather than index order; that is detected below and then put right.
         const bool narrow = V - T < (1u << 24);
-        // compaction without branches: a candidate that is not live goes to a slot
-        // behind the live ones, which nobody reads
+        // compaction without branches: a candidate that is not live goes to the
+        // lane's own slot behind the live ones, which nobody reads
         {
-            const uint32_t dump = (uint32_t)(2 * kWave + 2);
+            const uint32_t dump_c = (uint32_t)(kMaxLive + 4 + lane), dump_k = (uint32_t)(kMaxLive + 32 + lane);
             uint32_t pos = (uint32_t)before;
 #pragma unroll
             for (int q = 0; q < KC; ++q) {
                 const bool live = cv[q] > T;
-                const uint32_t at = live ? pos : dump;
                 u32x4 r;
                 r.x = f2u(cx[q]); r.y = f2u(cy[q]); r.z = f2u(cz[q]); r.w = cv[q];
-                lds_write16(cand_off + at * 16, r);
-                lds_write4(key_off + at * 4, ((cv[q] - T) << 7) | pos);
-                lds_write4(idx_off + at * 4, ci[q]);
+                lds_write16(cand_off + (live ? pos : dump_c) * 16, r);
+                lds_write4(key_off + (live ? pos : dump_k) * 4, ((cv[q] - T) << 8) | pos);
+                lds_write4(idx_off + (live ? pos : dump_c) * 4, ci[q]);
                 pos += live ? 1u : 0u;
             }
         }
         if (lane < 32) lds_write4(key_off + (total + lane) * 4, 0u);  // padding: below every key
         // the same wave wrote and now reads: LDS keeps its accesses in order
         FFPS_SUB(2);
-        // ---- order: every lane ranks its candidates (positions `lane` and
-        //      `lane + 64`) by counting the candidates that precede them ----
-        const int p1 = lane + kWave;
-        const bool h0 = lane < total, h1 = p1 < total;
-        const uint32_t q0 = h0 ? (uint32_t)lane : 0u, q1 = h1 ? (uint32_t)p1 : 0u;  // safe positions
-        u32x4 c0, c1;
-        u32x2 w0, w1;
-        uint32_t i0, i1;
-        lds_read_pair(c0, c1, w0, w1, i0, i1, cand_off + q0 * 16, cand_off + q1 * 16, key_off + q0 * 4,
-                      key_off + q1 * 4, idx_off + q0 * 4, idx_off + q1 * 4);
-        uint32_t o0 = h0 ? c0.w : 0u, o1 = h1 ? c1.w : 0u;  // values at the start of the round
+#ifdef FFPS_PROFILE
+        oc = clock64();
+#endif
+        // ---- order: every lane ranks its candidates (positions lane, lane + 64, ...)
+        //      by counting the candidates that precede them ----
+        const int nsets = (total + kWave - 1) / kWave;  // sets in use
+        bool h[kSets];          // this lane has a candidate in set s
+        uint32_t a_c[kSets], a_w[kSets], a_i[kSets];  // where to read it (position 0 if it has none)
+#pragma unroll
+        for (int s = 0; s < kSets; ++s) {
+            const int p = lane + s * kWave;
+            h[s] = p < total;
+            const uint32_t q = h[s] ? (uint32_t)p : 0u;
+            a_c[s] = cand_off + q * 16; a_w[s] = key_off + q * 4; a_i[s] = idx_off + q * 4;
+        }
+        u32x4 c[kSets];
+        u32x2 w[kSets];
+        uint32_t ix[kSets], o[kSets];  // index; value at the start of the round
+        lds_read_own(c, w, ix, a_c, a_w, a_i);
+#pragma unroll
+        for (int s = 0; s < kSets; ++s) o[s] = h[s] ? c[s].w : 0u;
         bool ties = false;
+        FFPS_ORD(0);
         // Candidates go to their places in the order: records {x, y, z, sequence
-        // number as a pick if no candidate ahead is passed over} (what the workers
-        // take), values and indices.  Every lane then takes candidates number `lane`
-        // (set 0) and `lane + 64` (set 1) of the order, and sees whether the
-        // candidate behind each of them has the same value.
-        auto place = [&](int r0, int r1) {
-            if (h0) {
-                c0.w = (uint32_t)(npicked + r0);
-                lds_write16(cand_off + r0 * 16, c0);
-                lds_write4(key_off + r0 * 4, o0);
-                lds_write4(idx_off + r0 * 4, i0);
-            }
-            if (h1) {
-                c1.w = (uint32_t)(npicked + r1);
-                lds_write16(cand_off + r1 * 16, c1);
-                lds_write4(key_off + r1 * 4, o1);
-                lds_write4(idx_off + r1 * 4, i1);
+        // number as a pick if no candidate ahead is passed over}, values and indices.
+        // Every lane then takes candidates number lane, lane + 64, ... of the order
+        // (sets 0, 1, ...) and sees whether the candidate behind each of them has
+        // the same value.
+        auto place = [&](const int (&r)[kSets]) {
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) {
+                if (h[s]) {
+                    c[s].w = (uint32_t)(npicked + r[s]);
+                    lds_write16(cand_off + r[s] * 16, c[s]);
+                    lds_write4(key_off + r[s] * 4, o[s]);
+                    lds_write4(idx_off + r[s] * 4, ix[s]);
+                }
             }
             if (lane == 0) lds_write4(key_off + total * 4, 0u);  // behind the last value
-            lds_read_pair(c0, c1, w0, w1, i0, i1, cand_off + q0 * 16, cand_off + q1 * 16,
-                          key_off + q0 * 4, key_off + q1 * 4, idx_off + q0 * 4, idx_off + q1 * 4);
-            o0 = h0 ? w0.x : 0u;
-            o1 = h1 ? w1.x : 0u;
-            ties = __builtin_amdgcn_ballot_w64((h0 && w0.y == w0.x) || (h1 && w1.y == w1.x)) != 0;
+            lds_read_own(c, w, ix, a_c, a_w, a_i);
+            bool tie = false;
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) {
+                o[s] = h[s] ? w[s].x : 0u;
+                tie = tie || (h[s] && w[s].y == w[s].x);
+            }
+            ties = __builtin_amdgcn_ballot_w64(tie) != 0;
         };
         // by (value descending, index ascending) on the full values: always right
         auto order_exact = [&]() {
-            const uint64_t key0 = ((uint64_t)o0 << 32) | ~i0, key1 = ((uint64_t)o1 << 32) | ~i1;
-            int r0 = 0, r1 = 0;
+            uint64_t key[kSets];
+            int r[kSets];
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) {
+                key[s] = ((uint64_t)o[s] << 32) | ~ix[s];
+                r[s] = 0;
+            }
             for (int j = 0; j < total; ++j) {
                 const uint64_t kj = ((uint64_t)lds_read4(key_off + j * 4) << 32) | ~lds_read4(idx_off + j * 4);
-                r0 += kj > key0 ? 1 : 0;
-                r1 += kj > key1 ? 1 : 0;
+#pragma unroll
+                for (int s = 0; s < kSets; ++s) r[s] += kj > key[s] ? 1 : 0;
             }
-            place(r0, r1);
+            place(r);
         };
+        if (TEAM) {
+            // the whole workgroup ranks when the 32-bit keys can be used; the two
+            // barriers are passed in any case
+            const uint32_t rank_off = lds_offset(L.rank);
+#pragma unroll
+            for (int s = 0; s < kSets; ++s)
+                if (h[s]) lds_write4(rank_off + (uint32_t)(lane + s * kWave) * 4, 0u);
+            if (lane == 0) lds_write4(lds_offset(&L.team_total), narrow ? (uint32_t)total : 0u);
+            team_barrier();
+            FFPS_ORD(1);
+            team_rank(L, lane, 0, team_waves);
+            FFPS_ORD(2);
+            team_barrier();
+            FFPS_ORD(3);
+        }
         if (narrow) {
-            const uint32_t key0 = ((o0 - T) << 7) | (uint32_t)lane, key1 = ((o1 - T) << 7) | (uint32_t)p1;
-            int r0 = 0, r1 = 0;
-            for (int j = 0; j < total; j += 32) {
-                // thirty-two keys per step, read by all lanes from the same addresses (a broadcast)
-                u32x4 k[8];
-                lds_read128(k, key_off + j * 4);
+            int r[kSets];
+            if (TEAM) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    r0 += k[e].x > key0 ? 1 : 0; r0 += k[e].y > key0 ? 1 : 0;
-                    r0 += k[e].z > key0 ? 1 : 0; r0 += k[e].w > key0 ? 1 : 0;
+                for (int s = 0; s < kSets; ++s)
+                    r[s] = h[s] ? (int)lds_read4(lds_offset(L.rank) + (uint32_t)(lane + s * kWave) * 4) : 0;
+            } else {
+                uint32_t key[kSets];
+#pragma unroll
+                for (int s = 0; s < kSets; ++s) {
+                    key[s] = ((o[s] - T) << 8) | (uint32_t)(lane + s * kWave);
+                    r[s] = 0;
                 }
-                if (total > kWave) {
+                for (int j = 0; j < total; j += 32) {
+                    // thirty-two keys per step, read by all lanes from the same addresses (a broadcast)
+                    u32x4 k[8];
+                    lds_read128(k, key_off + j * 4);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        r1 += k[e].x > key1 ? 1 : 0; r1 += k[e].y > key1 ? 1 : 0;
-                        r1 += k[e].z > key1 ? 1 : 0; r1 += k[e].w > key1 ? 1 : 0;
+                    for (int s = 0; s < kSets; ++s) {
+                        if (s < nsets) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                r[s] += k[e].x > key[s] ? 1 : 0; r[s] += k[e].y > key[s] ? 1 : 0;
+                                r[s] += k[e].z > key[s] ? 1 : 0; r[s] += k[e].w > key[s] ? 1 : 0;
+                            }
+                        }
                     }
                 }
             }
-            place(r0, r1);
-            if (ties) order_exact();  // the values are in LDS in order now: equal neighbours are ties
+            place(r);
+            FFPS_ORD(4);
+            // The values are in LDS in order now: equal neighbours are candidates of
+            // equal value, which the 32-bit keys put in position order where index
+            // order is wanted.  The values of a round lie in a narrow band, so among a
+            // hundred of them two that agree in every bit are common.  Two such
+            // neighbours change places when their indices say so; three or more in a
+            // row (rare) are left to the exact ordering.
+            if (ties) {
+                bool lng = false, mv = false;
+                int np[kSets];
+                // value and index of the candidate before each of this lane's, index of
+                // the one behind it (position 0 where there is none)
+                uint32_t nb[3 * kSets], na[3 * kSets];
+#pragma unroll
+                for (int s = 0; s < kSets; ++s) {
+                    const int p = lane + s * kWave;
+                    const uint32_t pb = h[s] && p > 0 ? (uint32_t)(p - 1) : 0u;
+                    const uint32_t pa = p + 1 < total ? (uint32_t)(p + 1) : 0u;
+                    na[3 * s] = key_off + pb * 4; na[3 * s + 1] = idx_off + pb * 4; na[3 * s + 2] = idx_off + pa * 4;
+                }
+                lds_read4x9(nb, na);
+#pragma unroll
+                for (int s = 0; s < kSets; ++s) {
+                    const int p = lane + s * kWave;
+                    np[s] = p;
+                    if (h[s]) {
+                        const uint32_t vb = nb[3 * s], ib = nb[3 * s + 1], ia = nb[3 * s + 2];
+                        const uint32_t va = w[s].y;  // keyw[p + 1]; zero behind the last one
+                        const bool eb = p > 0 && vb == o[s], ea = va == o[s];
+                        lng = lng || (eb && ea);
+                        if (ea && ia < ix[s]) np[s] = p + 1;       // the one behind has the lower index
+                        else if (eb && ib > ix[s]) np[s] = p - 1;  // the one before has the higher index
+                        mv = mv || np[s] != p;
+                    }
+                }
+#ifdef FFPS_PROFILE
+                if (prof && __builtin_amdgcn_ballot_w64(lng) != 0) prof->ev[3] += 1;
+#endif
+                if (__builtin_amdgcn_ballot_w64(lng) != 0) {
+                    order_exact();
+                } else if (__builtin_amdgcn_ballot_w64(mv) != 0) {
+                    place(np);
+                }
+            }
         } else {
-            lds_write4(key_off + q0 * 4, c0.w);  // order_exact reads the values there
-            if (h1) lds_write4(key_off + p1 * 4, c1.w);
+#pragma unroll
+            for (int s = 0; s < kSets; ++s)
+                if (h[s] || s == 0) lds_write4(a_w[s], c[s].w);  // order_exact reads the values there
             order_exact();
         }
-        const float x0 = u2f(c0.x), y0 = u2f(c0.y), z0 = u2f(c0.z);
-        const float x1 = u2f(c1.x), y1 = u2f(c1.y), z1 = u2f(c1.z);
-        uint32_t v0 = o0, v1 = o1;  // current values
+        float x[kSets], y[kSets], z[kSets];
+        uint32_t v[kSets];  // current values
+#pragma unroll
+        for (int s = 0; s < kSets; ++s) {
+            x[s] = u2f(c[s].x); y[s] = u2f(c[s].y); z[s] = u2f(c[s].z);
+            v[s] = o[s];
+        }
+        FFPS_ORD(5);
         FFPS_SUB(3);
 #ifdef FFPS_PROFILE
         const uint64_t lc0 = clock64();
 #endif
         // ---- replay, one set after the other ----
-        uint64_t gone0 = 0ull, gone1 = 0ull;  // candidates passed over
+        uint64_t gone[kSets] = {};  // candidates passed over
         int ngone = 0;
         bool stop = false;
         // Candidates [base, base + n) of the order are lanes 0 .. n-1 of a set.
         // Candidate base + li is pick number base + li - ngone of the round, so with
         // `cap` picks allowed the set ends at lane cap + ngone - base.  Returns the
         // number of candidates of the set that were dealt with.
-        auto run_set = [&](uint32_t &v, uint32_t o, float x, float y, float z, int base, int n,
-                           uint64_t &gone) {
+        auto run_set = [&](uint32_t &vs, uint32_t os, float xs, float ys, float zs, int base, int n,
+                           uint64_t &gs) {
             int li = 0;
             while (true) {
                 // the end of the set moves with the candidates passed over only when
@@ -663,48 +871,55 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 const bool soft = cap - base < n;
                 const int lend = soft ? (n < cap + ngone - base ? n : cap + ngone - base) : n;
                 if (li >= lend) break;
-                const int c = base + lane - ngone;  // this lane's candidate as a pick of the round
+                const int pc = base + lane - ngone;  // this lane's candidate as a pick of the round
                 uint64_t bit = 1ull << li;
-                const uint64_t gone_before = gone;
-                ordered_run(v, lane < lend ? o : 0xffffffffu, x, y, z, (uint32_t)(npicked + c),
-                            pk_off + (uint32_t)c * 16, bit, li, gone,
+                const uint64_t gone_before = gs;
+                ordered_run(vs, lane < lend ? os : 0xffffffffu, xs, ys, zs, (uint32_t)(npicked + pc),
+                            pk_off + (uint32_t)pc * 16, bit, li, gs,
                             (uint32_t)__builtin_amdgcn_readfirstlane((int)T),
                             __builtin_amdgcn_readfirstlane(lend),
                             __builtin_amdgcn_readfirstlane(soft ? 1 : 0));
-                ngone += __builtin_popcountll(gone ^ gone_before);
+                ngone += __builtin_popcountll(gs ^ gone_before);
                 if (li >= lend) break;
                 // candidate li has been lowered by a pick of this round
-                if ((uint32_t)readlane_i((int)v, li) > T) {
+                if ((uint32_t)readlane_i((int)vs, li) > T) {
                     stop = true;  // still a candidate, but maybe no longer the next one
                     break;
                 }
                 // out of this round: the candidates behind it become picks one number earlier
-                gone |= 1ull << li;
+                gs |= 1ull << li;
                 ++ngone;
                 ++li;
             }
             return li;
         };
-        const int nA = total < kWave ? total : kWave;
-        const int iA = run_set(v0, o0, x0, y0, z0, 0, nA, gone0);
-        int iB = 0;
-        if (!stop && iA == kWave && total > kWave && cap + ngone > kWave) {
-            // set 1 has not seen the picks of set 0 yet: apply them (the workers are
-            // busy with the same picks meanwhile)
-            // Eight slots per LDS read.  Slots behind the picks of this round hold
-            // picks of earlier rounds (or the seed point), which every value already
-            // reflects, so applying those again changes nothing.
-            const int done = kWave - ngone;
-            for (int c = 0; c < done; c += 8) {
-                u32x4 r[8];
-                lds_read128(r, pk_off + c * 16);
+        int dealt[kSets] = {};  // candidates of each set that were dealt with
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    v1 = f2u(min_dist(u2f(v1), sqdist(x1, y1, z1, u2f(r[e].x), u2f(r[e].y), u2f(r[e].z))));
+        for (int s = 0; s < kSets; ++s) {
+            const int base = s * kWave;
+            if (stop || base >= total || cap + ngone <= base) break;
+            if (s > 0) {
+                if (dealt[s - 1] < kWave) break;
+                // This set has not seen the picks of the sets before it: apply them (the
+                // workers are busy with the same picks meanwhile), eight slots per LDS
+                // read.  Slots behind the picks of this round hold picks of earlier
+                // rounds (or the seed point), which every value already reflects, so
+                // applying those again changes nothing.
+                const int done = base - ngone;
+                for (int k0 = 0; k0 < done; k0 += 8) {
+                    u32x4 rr[8];
+                    lds_read128(rr, pk_off + k0 * 16);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        v[s] = f2u(min_dist(u2f(v[s]), sqdist(x[s], y[s], z[s], u2f(rr[e].x), u2f(rr[e].y),
+                                                              u2f(rr[e].z))));
+                }
             }
-            iB = run_set(v1, o1, x1, y1, z1, kWave, total - kWave, gone1);
+            const int n = total - base < kWave ? total - base : kWave;
+            dealt[s] = run_set(v[s], o[s], x[s], y[s], z[s], base, n, gone[s]);
+            cnt += dealt[s];
         }
-        cnt = iA + iB - ngone;
+        cnt -= ngone;
 #ifdef FFPS_PROFILE
         if (prof) {
             prof->ev[0] += (uint32_t)total;
@@ -714,14 +929,17 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
 #endif
         // the candidates dealt with were picked unless passed over; the pick number
         // of one of them is its place minus the candidates passed over before it
-        const int g0 = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(gone0 >> 32),
-                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)gone0, 0u));
-        const int g1 = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(gone1 >> 32),
-                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)gone1, 0u));
-        if (lane < iA && !((gone0 >> lane) & 1ull)) res.pc[0] = lane - g0;
-        if (lane < iB && !((gone1 >> lane) & 1ull)) res.pc[1] = p1 - __builtin_popcountll(gone0) - g1;
-        res.pi[0] = i0; res.pi[1] = i1;
-        res.pv[0] = o0; res.pv[1] = o1;
+        int gone_before_set = 0;
+#pragma unroll
+        for (int s = 0; s < kSets; ++s) {
+            const int g = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(gone[s] >> 32),
+                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)gone[s], 0u));
+            if (lane < dealt[s] && !((gone[s] >> lane) & 1ull))
+                res.pc[s] = lane + s * kWave - gone_before_set - g;
+            gone_before_set += __builtin_popcountll(gone[s]);
+            res.pi[s] = ix[s];
+            res.pv[s] = o[s];
+        }
 #ifdef FFPS_PROFILE
         if (prof) {
             prof->loop[total <= kWave ? 0 : 2] += (uint32_t)(clock64() - lc0);
@@ -730,8 +948,13 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
 #endif
     } else {
         // a single pick (best candidate not above the bound, or cap 1), or more
-        // than 128 candidates above every threshold tried: work on all candidates
-        // of every lane
+        // than kMaxLive candidates above every threshold tried: work on all
+        // candidates of every lane
+        if (TEAM) {
+            if (lane == 0) lds_write4(lds_offset(&L.team_total), 0u);
+            team_barrier();
+            team_barrier();
+        }
         while (true) {
             uint32_t bv, bi;
             int bq;
@@ -757,7 +980,7 @@ __device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const 
                                              int npicked, int32_t *idx_out, float *md_out) {
     if (r.by_lane) {
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
+        for (int e = 0; e < kSets; ++e) {
             if (r.pc[e] >= 0) {
                 idx_out[npicked + r.pc[e]] = (int32_t)r.pi[e];
                 if (md_out) md_out[npicked + r.pc[e]] = u2f(r.pv[e]);
@@ -779,11 +1002,11 @@ __device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const 
 // the replay is still running).  Returns the picks of the round (1 .. cap; see
 // record_picks), or a count of -1 after setting *status when another unit's
 // record never arrived.
-template <int T>
+template <int T, bool TEAM = false>
 __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchange, int U, int unit0,
                                                       int nsub, int lane, uint32_t round,
                                                       const RoundInput<T> &in, int npicked, int cap,
-                                                      int *status, RoundProf *prof) {
+                                                      int *status, RoundProf *prof, int team_waves = 1) {
     static_assert(T == 2 || T == 3, "two or three candidates per unit");
     constexpr int NCH = chunks_of(T);
     constexpr int KC = T * kRPL;  // candidates per lane before compaction
@@ -875,7 +1098,7 @@ __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchang
         const uint32_t bnd = T == 2 ? r[0][q].z : r[NCH - 1][q].x;
         lb = umax(lb, present ? bnd : 0u);
     }
-    return replay_round<KC>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
+    return replay_round<KC, TEAM>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof, team_waves);
 }
 
 }  // namespace ffps

@@ -34,7 +34,7 @@ namespace {
 // Candidates a reporting unit contributes to a round.  Three were tried: more
 // picks per round, but a dearer round (larger records, a fourth reduction per
 // merge, half as many candidates again to count and compact) and slower overall.
-constexpr int kT = 2;
+constexpr int kT = 3;
 
 struct WaveTop {  // a worker wave's kT best points and the bound on its others
     TopK<kT> t;
@@ -208,6 +208,10 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
                 }
             }
             __syncthreads();  // wave tops ready for the communication wave
+            // ---- 1d. help to rank the candidates of the next round ----
+            team_barrier();  // the communication wave has the keys in place
+            team_rank(L, lane, wave, NWK + 1);
+            team_barrier();  // ranks complete
         }
         return;
     }
@@ -242,8 +246,8 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             }
             in.bound = o.t.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
-            res = exchange_round<kT>(L, a.exchange, G * NWK, w * NWK, NWK, lane, round, in, npicked,
-                                     cap, a.status, prof);
+            res = exchange_round<kT, true>(L, a.exchange, G * NWK, w * NWK, NWK, lane, round, in, npicked,
+                                           cap, a.status, prof, NWK + 1);
         } else {
             // ---- 2a. the workgroup's kT best + bound from the worker waves' ----
             const bool act = lane < NWK;
@@ -265,11 +269,18 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             }
             in.bound = g3.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
-            res = exchange_round<kT>(L, a.exchange, G, w, 1, lane, round, in, npicked, cap, a.status,
-                                     prof);
+            res = exchange_round<kT, true>(L, a.exchange, G, w, 1, lane, round, in, npicked, cap,
+                                           a.status, prof, NWK + 1);
         }
         const int cnt = res.cnt;
         if (cnt < 0) {
+            // the workers wait for the ranking: let them through with nothing to do
+            if (lane == 0) lds_write4(lds_offset(&L.team_total), 0u);
+            team_barrier();
+            team_barrier();
+#ifdef FFPS_PROFILE
+            if (prof && lane == 0)
+        #endif
             if (lane == 0) {
                 s_abort = 1;
                 u32x2 f;
@@ -292,13 +303,15 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         // exchange rounds this launch took (the largest count among its clouds)
         __hip_atomic_fetch_max(a.status + 1, (int)round, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #ifdef FFPS_PROFILE
-        if (cloud == 0)
+        if (cloud == 0) {
         for (int i = 0; i < 8; ++i) a.status[8 + i] = (int)prof_store.acc[i];
         for (int i = 0; i < 4; ++i) a.status[20 + i] = (int)prof_store.loop[i];
         for (int i = 0; i < 4; ++i) a.status[24 + i] = (int)prof_store.sub[i];
         for (int i = 0; i < 4; ++i) a.status[28 + i] = (int)prof_store.ev[i];
+        for (int i = 0; i < 6; ++i) a.status[32 + i] = (int)prof_store.ord[i];
         a.status[16] = (int)(wall_clock64() - prof_w0);       // 10 ns units
         a.status[17] = (int)((clock64() - prof_c0) >> 4);     // shader cycles / 16
+        }
 #endif
     }
 }

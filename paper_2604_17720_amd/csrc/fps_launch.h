@@ -7,7 +7,7 @@
 namespace ffps {
 
 #ifndef FFPS_MAX_PICKS
-#define FFPS_MAX_PICKS 128
+#define FFPS_MAX_PICKS 192
 #endif
 constexpr int kMaxPicksPerRound = FFPS_MAX_PICKS;  // picks one round may deliver
 
@@ -29,7 +29,7 @@ hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, const
 // ---- fps_grid.hip: clouds spread over the whole device, resident in registers ----
 constexpr int kMaxGridWG = 256;      // workgroups (one per CU) a launch may use
 // bytes of one cloud's exchange area: two buffers of four 16-byte chunks for each of 256 units
-constexpr size_t kExchangeBytesPerCloud = 2 * 4 * (size_t)kMaxGridWG * 16;
+constexpr size_t kExchangeBytesPerCloud = 2 * 6 * (size_t)kMaxGridWG * 16;
 size_t grid_exchange_bytes_per_cloud();  // the same value, as the kernels' own headers derive it
 long grid_capacity(int num_cu);          // largest N the register-resident grid kernel holds
 // How B clouds of N points are laid over the device: workgroups per cloud, and

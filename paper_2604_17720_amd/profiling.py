@@ -57,7 +57,7 @@ def _phases(args) -> None:
         fb.ffps_exact(x4, M, 0, var, workspace=ws)
         e1.record()
         torch.cuda.synchronize()
-        st = ws[:128].view(torch.int32).cpu().numpy().astype("int64")
+        st = ws[:256].view(torch.int32).cpu().numpy().astype("int64")
         r = int(st[1])
         cap = "library default" if picks == 0 else str(picks)
         print(f"## picks per round capped at {cap}: M = {M}, {e0.elapsed_time(e1):.2f} ms, {r} rounds, "
@@ -73,10 +73,14 @@ def _phases(args) -> None:
               f"compaction {st[26] / r:.0f}, ordering {st[27] / r:.0f}")
         if st[21] + st[23] > 0:
             print(f"- pick loop: {st[20] / max(st[21], 1):.0f} cycles per pick over {st[21]} picks with one "
-                  f"candidate per lane, {st[22] / max(st[23], 1):.0f} over {st[23]} picks with two")
+                  f"candidate per lane, {st[22] / max(st[23], 1):.0f} over {st[23]} picks with more")
+        print(f"- inside the ordering, shader cycles per round: own load {st[32] / r:.0f}, first barrier "
+              f"{st[33] / r:.0f}, ranking share {st[34] / r:.0f}, second barrier {st[35] / r:.0f}, placing "
+              f"{st[36] / r:.0f}, rest {st[37] / r:.0f}")
         print(f"- per round: {st[28] / r:.1f} live candidates, {st[29] / r:.1f} passed over, "
-              f"{st[30] / r:.2f} rounds ended early by a lowered candidate")
-        print(f"- rounds by path: one candidate per lane {st[13]}, two {st[14]}, general {r - st[13] - st[14]}")
+              f"{st[30] / r:.2f} rounds ended early by a lowered candidate, {st[31] / r:.3f} exact re-orderings "
+              f"(three or more equal values in a row)")
+        print(f"- rounds by path: up to 64 live candidates {st[13]}, more {st[14]}, general {r - st[13] - st[14]}")
         print(f"- kernel: {st[16] * 0.01:.1f} us wall, {st[17] * 16 / (st[16] * 10.0):.3f} GHz shader clock\n")
 
 
