@@ -300,12 +300,18 @@ struct RoundLds {
     // (one common entry would make every such write a 64-way bank conflict)
     __attribute__((aligned(16))) u32x4 cand[kMaxLive + 4 + kWave];  // {x, y, z, value; later sequence number}
     __attribute__((aligned(16))) uint32_t keyw[kMaxLive + 32 + kWave];  // 32-bit sort keys, zero-padded; later the values in order
-    uint32_t idxw[kMaxLive + 4 + kWave];                                // point indices
-    // ranking by the whole workgroup: how many keys there are to rank (0: none this
-    // round) and the ranks, which the waves add up
-    uint32_t team_total;
-    uint32_t rank[kMaxLive];
+    __attribute__((aligned(16))) uint32_t idxw[kMaxLive + 4 + kWave];   // point indices
+    // replay by the whole workgroup: number of live candidates (0: nothing to do this
+    // round) and the threshold, then for every candidate b three bit masks over the
+    // candidates a, in slices of 16: a lowers b to the threshold or below / a lowers b
+    // / a comes before b in the order; the first two only where a comes before b
+    __attribute__((aligned(16))) u32x2 key64[kMaxLive + 16];  // {complement of the index, value}: compares as the order does
+    __attribute__((aligned(8))) uint32_t team_total, team_T;
+    __attribute__((aligned(8))) uint16_t mask[3][kMaxLive][kMaxLive / 16];
 };
+constexpr uint32_t kMaskRow = (kMaxLive / 16) * 2;        // bytes of one candidate's mask
+constexpr uint32_t kMaskPlane = kMaxLive * kMaskRow;     // bytes of one of the three masks
+static_assert(kMaskRow == 24, "a mask row is read as three 8-byte words");
 
 // Counters of a profiling build (workgroup 0 only).
 struct RoundProf {
@@ -350,63 +356,88 @@ __device__ __forceinline__ void lds_read4x9(uint32_t (&r)[9], const uint32_t (&a
                  : "memory");
 }
 
-// Ranking of the live candidates by all W waves of a workgroup (the wave that
-// replays and the worker waves, which have nothing else to do at that point).
-// L.keyw[0 .. total) holds the unique 32-bit sort keys, zero-padded behind the
-// last one; the rank of a candidate is the number of keys above its own.  Wave
-// number wv counts, for the candidates lane, lane + 64, ... , the keys of its
-// share [wv * chunk, (wv + 1) * chunk) that are above theirs and adds the
-// counts to L.rank, which starts at zero.  Called by every wave between two
-// workgroup barriers: the keys are in place before the first, the ranks are
-// complete after the second.
-__device__ __forceinline__ void team_rank(RoundLds &L, int lane, int wv_in, int W) {
-    const int total = __builtin_amdgcn_readfirstlane((int)lds_read4(lds_offset(&L.team_total)));
-    const int wv = __builtin_amdgcn_readfirstlane(wv_in);
-    if (total == 0) return;
-    const uint32_t key_off = lds_offset(L.keyw), rank_off = lds_offset(L.rank);
-    const int nsets = (total + kWave - 1) / kWave;
-    const int chunk = ((total + W - 1) / W + 3) & ~3;  // keys per wave, a multiple of four
-    const int j0 = wv * chunk;
-    if (j0 >= total) return;
-    const int j1 = j0 + chunk < total ? j0 + chunk : total;
-    // own keys (a lane without a candidate in set s reads padding or a key of
-    // another set, and its count goes nowhere) and the first sixteen keys of the
-    // share in one go
-    static_assert(kSets == 3, "three own keys are read");
-    uint32_t key[kSets];
-    int r[kSets] = {};
-    u32x4 ka, kb, kc, kd;
-    asm volatile("ds_read_b32 %0, %7\n\tds_read_b32 %1, %7 offset:256\n\tds_read_b32 %2, %7 offset:512\n\t"
-                 "ds_read_b128 %3, %8\n\tds_read_b128 %4, %8 offset:16\n\t"
-                 "ds_read_b128 %5, %8 offset:32\n\tds_read_b128 %6, %8 offset:48\n\t"
+// One more bit for a mask that is built from its most significant end: m = 2 m + c,
+// where c is a comparison result of this lane (a ballot).
+__device__ __forceinline__ void push_bit(uint32_t &m, uint64_t c) {
+    asm("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(m) : "s"(c) : "vcc");
+}
+// The three masks of one candidate: 3 x 24 bytes, one wait.
+__device__ __forceinline__ void lds_read_masks(uint32_t (&k)[6], uint32_t (&l)[6], uint32_t (&b)[6], uint32_t off) {
+    u32x2 r[9];
+    asm volatile("ds_read_b64 %0, %9\n\tds_read_b64 %1, %9 offset:8\n\tds_read_b64 %2, %9 offset:16\n\t"
+                 "ds_read_b64 %3, %9 offset:4608\n\tds_read_b64 %4, %9 offset:4616\n\t"
+                 "ds_read_b64 %5, %9 offset:4624\n\t"
+                 "ds_read_b64 %6, %9 offset:9216\n\tds_read_b64 %7, %9 offset:9224\n\t"
+                 "ds_read_b64 %8, %9 offset:9232\n\t"
                  "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(key[0]), "=&v"(key[1]), "=&v"(key[2]), "=&v"(ka), "=&v"(kb), "=&v"(kc), "=&v"(kd)
-                 : "v"(key_off + (uint32_t)lane * 4), "v"(key_off + (uint32_t)j0 * 4)
-                 : "memory");
-    for (int j = j0; j < j1; j += 16) {
-        // sixteen keys per step (those behind the wave's share or behind the last
-        // key are skipped or zero), read by all lanes from the same addresses
-        if (j > j0) lds_read64(ka, kb, kc, kd, key_off + j * 4);
-        const uint32_t kk[16] = {ka.x, ka.y, ka.z, ka.w, kb.x, kb.y, kb.z, kb.w,
-                                 kc.x, kc.y, kc.z, kc.w, kd.x, kd.y, kd.z, kd.w};
+                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]),
+                   "=&v"(r[7]), "=&v"(r[8])
+                 : "v"(off) : "memory");
+    static_assert(kMaskPlane == 4608, "offsets of the second and third mask");
 #pragma unroll
-        for (int g = 0; g < 16; g += 4) {
-            if (j + g < j1) {  // shares are multiples of four keys; the last one ends in zeros
-#pragma unroll
-                for (int s = 0; s < kSets; ++s) {
-                    if (s < nsets) {
-#pragma unroll
-                        for (int e = g; e < g + 4; ++e) r[s] += kk[e] > key[s] ? 1 : 0;
-                    }
-                }
-            }
-        }
+    for (int i = 0; i < 3; ++i) {
+        k[2 * i] = r[i].x; k[2 * i + 1] = r[i].y;
+        l[2 * i] = r[3 + i].x; l[2 * i + 1] = r[3 + i].y;
+        b[2 * i] = r[6 + i].x; b[2 * i + 1] = r[6 + i].y;
     }
+}
+__device__ __forceinline__ void lds_write2b(uint32_t off, uint32_t v) {
+    asm volatile("ds_write_b16 %0, %1" : : "v"(off), "v"(v) : "memory");
+}
+
+// What the picks of a round do to each other, worked out by all W waves of a
+// workgroup (the wave that replays and the worker waves, which have nothing
+// else to do at that point).  L.cand[0 .. total) holds the live candidates
+// {x, y, z, value} in any order and L.key64 {complement of the index, value},
+// followed by at least 15 entries of value 0.  For candidates a and b let d be their squared
+// distance (the individually rounded operations of sqdist, which give the same
+// bits either way round) and let "a before b" mean that a precedes b in the
+// order (value descending, index ascending).  A task takes a slice of 16
+// candidates a and a set of 64 candidates b, one per lane, and writes 16 bits of
+// each of b's masks: d <= T (picking a would put b out of this round); d < value
+// of b (picking a would lower b); a before b.  Bit 31 - (a mod 32) of 32-bit
+// word a / 32 stands for a.  Tasks are dealt out to the waves in turn.  Called by
+// every wave between two workgroup barriers.
+__device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, int W) {
+    const u32x2 hdr = lds_read8(lds_offset(&L.team_total));
+    const int total = __builtin_amdgcn_readfirstlane((int)hdr.x);
+    if (total == 0) return;
+    const uint32_t T = (uint32_t)__builtin_amdgcn_readfirstlane((int)hdr.y);
+    const int nsl = (total + 15) >> 4, nsets = (total + kWave - 1) / kWave;
+    const uint32_t mask_off = lds_offset(L.mask);
+    int sl = __builtin_amdgcn_readfirstlane(wv_in), set = 0;
+    while (true) {
+        while (sl >= nsl) { sl -= nsl; ++set; }
+        if (set >= nsets) break;
+        // Plain loads, all of a task's up front, so that they are in flight together.
+        // The arrays were written before the barrier.
+        const int b = set * kWave + lane;
+        const u32x4 cb = L.cand[b];
+        const u32x2 kb2 = L.key64[b];
+        u32x4 ra[16];
+        u32x2 ka2[16];
 #pragma unroll
-    for (int s = 0; s < kSets; ++s) {
-        if (s < nsets && lane + s * kWave < total)
-            asm volatile("ds_add_u32 %0, %1" : : "v"(rank_off + (uint32_t)(lane + s * kWave) * 4),
-                         "v"((uint32_t)r[s]) : "memory");
+        for (int e = 0; e < 16; ++e) {
+            ra[e] = L.cand[sl * 16 + e];  // the same address in all lanes
+            ka2[e] = L.key64[sl * 16 + e];
+        }
+        const float xb = u2f(cb.x), yb = u2f(cb.y), zb = u2f(cb.z);
+        const uint64_t kb = ((uint64_t)kb2.y << 32) | kb2.x;
+        uint32_t mk = 0u, ml = 0u, mb = 0u;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const uint64_t ka = ((uint64_t)ka2[e].y << 32) | ka2[e].x;
+            const uint32_t d = f2u(sqdist(xb, yb, zb, u2f(ra[e].x), u2f(ra[e].y), u2f(ra[e].z)));
+            push_bit(mb, __builtin_amdgcn_ballot_w64(ka > kb));
+            push_bit(mk, __builtin_amdgcn_ballot_w64(d <= T));
+            push_bit(ml, __builtin_amdgcn_ballot_w64(d < kb2.y));
+        }
+        // two slices share a 32-bit word, the earlier one in its upper half
+        const uint32_t at = mask_off + (uint32_t)b * kMaskRow + (uint32_t)(sl ^ 1) * 2;
+        lds_write2b(at, mk);
+        lds_write2b(at + kMaskPlane, ml);
+        lds_write2b(at + 2 * kMaskPlane, mb);
+        sl += W;
     }
 }
 
@@ -520,8 +551,8 @@ struct RoundResult {
 __device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const RoundResult &r,
                                              int npicked, int32_t *idx_out, float *md_out);
 
-// With TEAM the other waves of the workgroup take part in the ranking: they
-// wait at a workgroup barrier after handing in their reports, call team_rank
+// With TEAM the other waves of the workgroup take part in the replay: they
+// wait at a workgroup barrier after handing in their reports, call team_matrix
 // and pass a second barrier, every round; this function passes the same two
 // barriers exactly once, whatever path the round takes.
 template <int KC, bool TEAM = false>
@@ -677,6 +708,11 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 lds_write16(cand_off + (live ? pos : dump_c) * 16, r);
                 lds_write4(key_off + (live ? pos : dump_k) * 4, ((cv[q] - T) << 8) | pos);
                 lds_write4(idx_off + (live ? pos : dump_c) * 4, ci[q]);
+                if (TEAM && live) {
+                    u32x2 k2;
+                    k2.x = ~ci[q]; k2.y = cv[q];
+                    lds_write8(lds_offset(L.key64) + pos * 8, k2);
+                }
                 pos += live ? 1u : 0u;
             }
         }
@@ -704,8 +740,140 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
         lds_read_own(c, w, ix, a_c, a_w, a_i);
 #pragma unroll
         for (int s = 0; s < kSets; ++s) o[s] = h[s] ? c[s].w : 0u;
-        bool ties = false;
         FFPS_ORD(0);
+        if constexpr (TEAM) {
+            // ---- replay by the whole workgroup: no order, no pick after pick.  The
+            //      other waves work out, for every pair of live candidates, which one
+            //      comes first and what picking it does to the other (team_matrix).
+            //      Candidate b is a pick of this round when no pick before it lowers
+            //      it; it is out of the round when a pick before it lowers it to the
+            //      threshold or below; otherwise a pick lowers it to a value that is
+            //      still live, and the round ends before it.  Which candidates are
+            //      picks follows from the candidates before them alone, so starting
+            //      from "all of them" and applying the rule to every candidate at once
+            //      settles one more candidate of the order per pass at least, and in
+            //      practice all of them after a few passes. ----
+            if (lane < 16) {
+                // entries of value 0 behind the last candidate: they come after every
+                // live one, which keeps their bits out of the masks
+                u32x4 zr;
+                zr.x = 0u; zr.y = 0u; zr.z = 0u; zr.w = 0u;
+                lds_write16(cand_off + (uint32_t)(total + lane) * 16, zr);
+                u32x2 z2;
+                z2.x = 0u; z2.y = 0u;
+                lds_write8(lds_offset(L.key64) + (uint32_t)(total + lane) * 8, z2);
+            }
+            if (lane == 0) {
+                u32x2 hd;
+                hd.x = (uint32_t)total; hd.y = T;
+                lds_write8(lds_offset(&L.team_total), hd);
+            }
+            team_barrier();
+            FFPS_ORD(1);
+            team_matrix(L, lane, 0, team_waves);
+            FFPS_ORD(2);
+            team_barrier();
+            FFPS_ORD(3);
+            uint32_t KB[kSets][6], LB[kSets][6], BB[kSets][6];
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) {
+#pragma unroll
+                for (int wd = 0; wd < 6; ++wd) { KB[s][wd] = 0u; LB[s][wd] = 0u; BB[s][wd] = 0u; }
+                if (s < nsets) {
+                    lds_read_masks(KB[s], LB[s], BB[s], lds_offset(L.mask) + (uint32_t)(lane + s * kWave) * kMaskRow);
+#pragma unroll
+                    for (int wd = 0; wd < 6; ++wd) { KB[s][wd] &= BB[s][wd]; LB[s][wd] &= BB[s][wd]; }
+                }
+            }
+            // a set of candidates as mask words (bit 31 - (a mod 32) of word a / 32)
+            auto to_words = [&](const uint64_t (&m)[kSets], uint32_t (&wds)[6]) {
+#pragma unroll
+                for (int s = 0; s < kSets; ++s) {
+                    wds[2 * s] = __builtin_bitreverse32((uint32_t)m[s]);
+                    wds[2 * s + 1] = __builtin_bitreverse32((uint32_t)(m[s] >> 32));
+                }
+            };
+            auto hits = [&](const uint32_t (&m)[6], const uint32_t (&wds)[6]) {
+                uint32_t acc = 0u;
+#pragma unroll
+                for (int wd = 0; wd < 6; ++wd) acc |= m[wd] & wds[wd];
+                return acc != 0u;
+            };
+            uint64_t pm[kSets];
+            uint32_t P[6];
+            bool pk[kSets];
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) {
+                pk[s] = h[s];
+                pm[s] = __builtin_amdgcn_ballot_w64(h[s]);
+            }
+            to_words(pm, P);
+            const int nlive = total;
+            for (int pass = 0; pass <= nlive; ++pass) {
+                uint32_t Q[6];
+#pragma unroll
+                for (int s = 0; s < kSets; ++s) {
+                    pk[s] = h[s] && !hits(KB[s], P);
+                    pm[s] = __builtin_amdgcn_ballot_w64(pk[s]);
+                }
+                to_words(pm, Q);
+                bool same = true;
+#pragma unroll
+                for (int wd = 0; wd < 6; ++wd) {
+                    same = same && Q[wd] == P[wd];
+                    P[wd] = Q[wd];
+                }
+                if (same) break;
+            }
+            // the round ends before the first candidate that a pick lowers without
+            // putting it out of the round
+            bool wounded[kSets];
+            uint64_t wm[kSets];
+            uint32_t Wd[6], F[6];
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) {
+                wounded[s] = pk[s] && hits(LB[s], P);
+                wm[s] = __builtin_amdgcn_ballot_w64(wounded[s]);
+            }
+            to_words(wm, Wd);
+            const bool ended = (wm[0] | wm[1] | wm[2]) != 0;
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) {
+                pk[s] = pk[s] && !wounded[s] && !(ended && hits(BB[s], Wd));
+                pm[s] = __builtin_amdgcn_ballot_w64(pk[s]);
+            }
+            to_words(pm, F);
+            int npk = 0;
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) npk += __builtin_popcountll(pm[s]);
+            cnt = npk < cap ? npk : cap;
+            // a pick's number within the round: the picks before it
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) {
+                int ord = 0;
+#pragma unroll
+                for (int wd = 0; wd < 6; ++wd) ord += __builtin_popcount(BB[s][wd] & F[wd]);
+                const bool sel = pk[s] && ord < cap;
+                if (sel) {
+                    u32x4 rec = c[s];
+                    rec.w = (uint32_t)(npicked + ord);
+                    lds_write16(pk_off + (uint32_t)ord * 16, rec);
+                }
+                res.pc[s] = sel ? ord : -1;
+                res.pi[s] = ix[s];
+                res.pv[s] = o[s];
+            }
+            FFPS_ORD(4);
+            FFPS_SUB(3);
+#ifdef FFPS_PROFILE
+            if (prof) {
+                prof->ev[0] += (uint32_t)total;
+                prof->ev[2] += ended ? 1u : 0u;
+                prof->loop[total <= kWave ? 1 : 3] += cnt;
+            }
+#endif
+        } else {
+        bool ties = false;
         // Candidates go to their places in the order: records {x, y, z, sequence
         // number as a pick if no candidate ahead is passed over}, values and indices.
         // Every lane then takes candidates number lane, lane + 64, ... of the order
@@ -747,28 +915,9 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             }
             place(r);
         };
-        if (TEAM) {
-            // the whole workgroup ranks when the 32-bit keys can be used; the two
-            // barriers are passed in any case
-            const uint32_t rank_off = lds_offset(L.rank);
-#pragma unroll
-            for (int s = 0; s < kSets; ++s)
-                if (h[s]) lds_write4(rank_off + (uint32_t)(lane + s * kWave) * 4, 0u);
-            if (lane == 0) lds_write4(lds_offset(&L.team_total), narrow ? (uint32_t)total : 0u);
-            team_barrier();
-            FFPS_ORD(1);
-            team_rank(L, lane, 0, team_waves);
-            FFPS_ORD(2);
-            team_barrier();
-            FFPS_ORD(3);
-        }
         if (narrow) {
             int r[kSets];
-            if (TEAM) {
-#pragma unroll
-                for (int s = 0; s < kSets; ++s)
-                    r[s] = h[s] ? (int)lds_read4(lds_offset(L.rank) + (uint32_t)(lane + s * kWave) * 4) : 0;
-            } else {
+            {
                 uint32_t key[kSets];
 #pragma unroll
                 for (int s = 0; s < kSets; ++s) {
@@ -946,6 +1095,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             prof->loop[total <= kWave ? 1 : 3] += cnt;
         }
 #endif
+        }  // the wave's own ordered replay
     } else {
         // a single pick (best candidate not above the bound, or cap 1), or more
         // than kMaxLive candidates above every threshold tried: work on all

@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             __syncthreads();  // wave tops ready for the communication wave
             // ---- 1d. help to rank the candidates of the next round ----
             team_barrier();  // the communication wave has the keys in place
-            team_rank(L, lane, wave, NWK + 1);
+            team_matrix(L, lane, wave, NWK + 1);
             team_barrier();  // ranks complete
         }
         return;
