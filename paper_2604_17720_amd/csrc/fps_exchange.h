@@ -22,6 +22,7 @@
 // assigned to units in any way; candidates carry their indices, and equal
 // values are detected and resolved on the index wherever they can occur.
 #pragma once
+#include <type_traits>
 #include "fps_device.h"
 #include "fps_launch.h"
 
@@ -202,6 +203,16 @@ __device__ __forceinline__ void lds_read_own(u32x4 (&c)[3], u32x2 (&w)[3], uint3
                    "v"(a_i[0]), "v"(a_i[1]), "v"(a_i[2])
                  : "memory");
 }
+// The records of three candidates and their 8-byte keys, all reads in flight together.
+__device__ __forceinline__ void lds_read_own_keys(u32x4 (&c)[3], u32x2 (&k)[3], const uint32_t (&a_c)[3],
+                                                  const uint32_t (&a_k)[3]) {
+    asm volatile("ds_read_b128 %0, %6\n\tds_read_b128 %1, %7\n\tds_read_b128 %2, %8\n\t"
+                 "ds_read_b64 %3, %9\n\tds_read_b64 %4, %10\n\tds_read_b64 %5, %11\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(c[0]), "=&v"(c[1]), "=&v"(c[2]), "=&v"(k[0]), "=&v"(k[1]), "=&v"(k[2])
+                 : "v"(a_c[0]), "v"(a_c[1]), "v"(a_c[2]), "v"(a_k[0]), "v"(a_k[1]), "v"(a_k[2])
+                 : "memory");
+}
 __device__ __forceinline__ void lds_write4(uint32_t off, uint32_t v) {
     asm volatile("ds_write_b32 %0, %1" : : "v"(off), "v"(v) : "memory");
 }
@@ -305,7 +316,7 @@ struct RoundLds {
     // round) and the threshold, then for every candidate b three bit masks over the
     // candidates a, in slices of 16: a lowers b to the threshold or below / a lowers b
     // / a comes before b in the order; the first two only where a comes before b
-    __attribute__((aligned(16))) u32x2 key64[kMaxLive + 16];  // {complement of the index, value}: compares as the order does
+    __attribute__((aligned(16))) u32x2 key64[kMaxLive + 4 + kWave];  // {complement of the index, value}: compares as the order does
     __attribute__((aligned(8))) uint32_t team_total, team_T;
     __attribute__((aligned(8))) uint16_t mask[3][kMaxLive][kMaxLive / 16];
 };
@@ -429,9 +440,12 @@ __device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, in
             const uint64_t ka = ((uint64_t)ka2[e].y << 32) | ka2[e].x;
             const uint32_t d = f2u(sqdist(xb, yb, zb, u2f(ra[e].x), u2f(ra[e].y), u2f(ra[e].z)));
             push_bit(mb, __builtin_amdgcn_ballot_w64(ka > kb));
-            push_bit(mk, __builtin_amdgcn_ballot_w64(d <= T));
-            push_bit(ml, __builtin_amdgcn_ballot_w64(d < kb2.y));
+            // values are bit patterns of non-negative numbers: the sign of a difference
+            // is the comparison, and it goes into the mask with one funnel shift
+            mk = __builtin_amdgcn_alignbit(mk, T - d, 31);        // T < d, turned round below
+            ml = __builtin_amdgcn_alignbit(ml, d - kb2.y, 31);    // d < value of b
         }
+        mk = ~mk;
         // two slices share a 32-bit word, the earlier one in its upper half
         const uint32_t at = mask_off + (uint32_t)b * kMaskRow + (uint32_t)(sl ^ 1) * 2;
         lds_write2b(at, mk);
@@ -706,17 +720,18 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 u32x4 r;
                 r.x = f2u(cx[q]); r.y = f2u(cy[q]); r.z = f2u(cz[q]); r.w = cv[q];
                 lds_write16(cand_off + (live ? pos : dump_c) * 16, r);
-                lds_write4(key_off + (live ? pos : dump_k) * 4, ((cv[q] - T) << 8) | pos);
-                lds_write4(idx_off + (live ? pos : dump_c) * 4, ci[q]);
-                if (TEAM && live) {
+                if constexpr (TEAM) {
                     u32x2 k2;
                     k2.x = ~ci[q]; k2.y = cv[q];
-                    lds_write8(lds_offset(L.key64) + pos * 8, k2);
+                    lds_write8(lds_offset(L.key64) + (live ? pos : dump_c) * 8, k2);
+                } else {
+                    lds_write4(key_off + (live ? pos : dump_k) * 4, ((cv[q] - T) << 8) | pos);
+                    lds_write4(idx_off + (live ? pos : dump_c) * 4, ci[q]);
                 }
                 pos += live ? 1u : 0u;
             }
         }
-        if (lane < 32) lds_write4(key_off + (total + lane) * 4, 0u);  // padding: below every key
+        if (!TEAM && lane < 32) lds_write4(key_off + (total + lane) * 4, 0u);  // padding: below every key
         // the same wave wrote and now reads: LDS keeps its accesses in order
         FFPS_SUB(2);
 #ifdef FFPS_PROFILE
@@ -737,7 +752,17 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
         u32x4 c[kSets];
         u32x2 w[kSets];
         uint32_t ix[kSets], o[kSets];  // index; value at the start of the round
-        lds_read_own(c, w, ix, a_c, a_w, a_i);
+        if constexpr (TEAM) {
+            u32x2 k2[kSets];
+            uint32_t a_k[kSets];
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) a_k[s] = lds_offset(L.key64) + (h[s] ? (uint32_t)(lane + s * kWave) : 0u) * 8;
+            lds_read_own_keys(c, k2, a_c, a_k);
+#pragma unroll
+            for (int s = 0; s < kSets; ++s) ix[s] = ~k2[s].x;
+        } else {
+            lds_read_own(c, w, ix, a_c, a_w, a_i);
+        }
 #pragma unroll
         for (int s = 0; s < kSets; ++s) o[s] = h[s] ? c[s].w : 0u;
         FFPS_ORD(0);
@@ -774,95 +799,106 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             FFPS_ORD(2);
             team_barrier();
             FFPS_ORD(3);
-            uint32_t KB[kSets][6], LB[kSets][6], BB[kSets][6];
+            // The rest for NS sets in use (known when compiling, so that every loop
+            // below is unrolled and the words of the sets not in use are not touched).
+            bool ended = false;
+            auto settle = [&](auto ns_tag) {
+                constexpr int NS = decltype(ns_tag)::value;
+                constexpr int NW = 2 * NS;
+                uint32_t KB[NS][6], LB[NS][6], BB[NS][6];
 #pragma unroll
-            for (int s = 0; s < kSets; ++s) {
-#pragma unroll
-                for (int wd = 0; wd < 6; ++wd) { KB[s][wd] = 0u; LB[s][wd] = 0u; BB[s][wd] = 0u; }
-                if (s < nsets) {
+                for (int s = 0; s < NS; ++s)
                     lds_read_masks(KB[s], LB[s], BB[s], lds_offset(L.mask) + (uint32_t)(lane + s * kWave) * kMaskRow);
 #pragma unroll
-                    for (int wd = 0; wd < 6; ++wd) { KB[s][wd] &= BB[s][wd]; LB[s][wd] &= BB[s][wd]; }
-                }
-            }
-            // a set of candidates as mask words (bit 31 - (a mod 32) of word a / 32)
-            auto to_words = [&](const uint64_t (&m)[kSets], uint32_t (&wds)[6]) {
+                for (int s = 0; s < NS; ++s) {
 #pragma unroll
-                for (int s = 0; s < kSets; ++s) {
-                    wds[2 * s] = __builtin_bitreverse32((uint32_t)m[s]);
-                    wds[2 * s + 1] = __builtin_bitreverse32((uint32_t)(m[s] >> 32));
+                    for (int wd = 0; wd < NW; ++wd) { KB[s][wd] &= BB[s][wd]; LB[s][wd] &= BB[s][wd]; }
+                }
+                // a set of candidates as mask words (bit 31 - (a mod 32) of word a / 32)
+                auto to_words = [&](const uint64_t (&m)[NS], uint32_t (&wds)[NW]) {
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) {
+                        wds[2 * s] = __builtin_bitreverse32((uint32_t)m[s]);
+                        wds[2 * s + 1] = __builtin_bitreverse32((uint32_t)(m[s] >> 32));
+                    }
+                };
+                auto hits = [&](const uint32_t (&m)[6], const uint32_t (&wds)[NW]) {
+                    uint32_t acc = 0u;
+#pragma unroll
+                    for (int wd = 0; wd < NW; ++wd) acc |= m[wd] & wds[wd];
+                    return acc != 0u;
+                };
+                uint64_t pm[NS];
+                uint32_t P[NW];
+                bool pk[NS];
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    pk[s] = h[s];
+                    pm[s] = __builtin_amdgcn_ballot_w64(h[s]);
+                }
+                to_words(pm, P);
+                for (int pass = 0; pass <= total; ++pass) {
+                    uint32_t Q[NW];
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) {
+                        pk[s] = h[s] && !hits(KB[s], P);
+                        pm[s] = __builtin_amdgcn_ballot_w64(pk[s]);
+                    }
+                    to_words(pm, Q);
+                    bool same = true;
+#pragma unroll
+                    for (int wd = 0; wd < NW; ++wd) {
+                        same = same && Q[wd] == P[wd];
+                        P[wd] = Q[wd];
+                    }
+                    if (same) break;
+                }
+                // the round ends before the first candidate that a pick lowers without
+                // putting it out of the round
+                bool wounded[NS];
+                uint64_t wm[NS], any_w = 0;
+                uint32_t Wd[NW], F[NW];
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    wounded[s] = pk[s] && hits(LB[s], P);
+                    wm[s] = __builtin_amdgcn_ballot_w64(wounded[s]);
+                    any_w |= wm[s];
+                }
+                ended = any_w != 0;
+                if (ended) {
+                    to_words(wm, Wd);
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) {
+                        pk[s] = pk[s] && !wounded[s] && !hits(BB[s], Wd);
+                        pm[s] = __builtin_amdgcn_ballot_w64(pk[s]);
+                    }
+                }
+                to_words(pm, F);
+                int npk = 0;
+#pragma unroll
+                for (int s = 0; s < NS; ++s) npk += __builtin_popcountll(pm[s]);
+                cnt = npk < cap ? npk : cap;
+                // a pick's number within the round: the picks before it
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    int ord = 0;
+#pragma unroll
+                    for (int wd = 0; wd < NW; ++wd) ord += __builtin_popcount(BB[s][wd] & F[wd]);
+                    const bool sel = pk[s] && ord < cap;
+                    if (sel) {
+                        u32x4 rec = c[s];
+                        rec.w = (uint32_t)(npicked + ord);
+                        lds_write16(pk_off + (uint32_t)ord * 16, rec);
+                    }
+                    res.pc[s] = sel ? ord : -1;
+                    res.pi[s] = ix[s];
+                    res.pv[s] = o[s];
                 }
             };
-            auto hits = [&](const uint32_t (&m)[6], const uint32_t (&wds)[6]) {
-                uint32_t acc = 0u;
-#pragma unroll
-                for (int wd = 0; wd < 6; ++wd) acc |= m[wd] & wds[wd];
-                return acc != 0u;
-            };
-            uint64_t pm[kSets];
-            uint32_t P[6];
-            bool pk[kSets];
-#pragma unroll
-            for (int s = 0; s < kSets; ++s) {
-                pk[s] = h[s];
-                pm[s] = __builtin_amdgcn_ballot_w64(h[s]);
-            }
-            to_words(pm, P);
-            const int nlive = total;
-            for (int pass = 0; pass <= nlive; ++pass) {
-                uint32_t Q[6];
-#pragma unroll
-                for (int s = 0; s < kSets; ++s) {
-                    pk[s] = h[s] && !hits(KB[s], P);
-                    pm[s] = __builtin_amdgcn_ballot_w64(pk[s]);
-                }
-                to_words(pm, Q);
-                bool same = true;
-#pragma unroll
-                for (int wd = 0; wd < 6; ++wd) {
-                    same = same && Q[wd] == P[wd];
-                    P[wd] = Q[wd];
-                }
-                if (same) break;
-            }
-            // the round ends before the first candidate that a pick lowers without
-            // putting it out of the round
-            bool wounded[kSets];
-            uint64_t wm[kSets];
-            uint32_t Wd[6], F[6];
-#pragma unroll
-            for (int s = 0; s < kSets; ++s) {
-                wounded[s] = pk[s] && hits(LB[s], P);
-                wm[s] = __builtin_amdgcn_ballot_w64(wounded[s]);
-            }
-            to_words(wm, Wd);
-            const bool ended = (wm[0] | wm[1] | wm[2]) != 0;
-#pragma unroll
-            for (int s = 0; s < kSets; ++s) {
-                pk[s] = pk[s] && !wounded[s] && !(ended && hits(BB[s], Wd));
-                pm[s] = __builtin_amdgcn_ballot_w64(pk[s]);
-            }
-            to_words(pm, F);
-            int npk = 0;
-#pragma unroll
-            for (int s = 0; s < kSets; ++s) npk += __builtin_popcountll(pm[s]);
-            cnt = npk < cap ? npk : cap;
-            // a pick's number within the round: the picks before it
-#pragma unroll
-            for (int s = 0; s < kSets; ++s) {
-                int ord = 0;
-#pragma unroll
-                for (int wd = 0; wd < 6; ++wd) ord += __builtin_popcount(BB[s][wd] & F[wd]);
-                const bool sel = pk[s] && ord < cap;
-                if (sel) {
-                    u32x4 rec = c[s];
-                    rec.w = (uint32_t)(npicked + ord);
-                    lds_write16(pk_off + (uint32_t)ord * 16, rec);
-                }
-                res.pc[s] = sel ? ord : -1;
-                res.pi[s] = ix[s];
-                res.pv[s] = o[s];
-            }
+            static_assert(kSets == 3, "one case per number of sets");
+            if (nsets == 1) settle(std::integral_constant<int, 1>{});
+            else if (nsets == 2) settle(std::integral_constant<int, 2>{});
+            else settle(std::integral_constant<int, 3>{});
             FFPS_ORD(4);
             FFPS_SUB(3);
 #ifdef FFPS_PROFILE

@@ -62,7 +62,7 @@ __host__ __device__ constexpr int grid_waves(int nwk) { return nwk + 1; }
 
 template <int NWK, int P>
 __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_in) {
-    static_assert(NWK == 3 || NWK == 7 || NWK == 15, "four, eight or sixteen waves in all");
+    static_assert(NWK == 3 || NWK == 7, "four or eight waves in all");
     __shared__ WaveTop wtop[NWK];
     __shared__ RoundLds L;
     // {batch id, picks emitted in total once that batch is complete}, one 8-byte word
@@ -131,34 +131,27 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             // padding: value 0 and an index beyond every real one, never preferred
             m[j] = ok ? __builtin_inff() : 0.f;
         }
-        int applied = 0;  // picks applied so far = sequence number of the next pick
-        for (int batch = 0;; ++batch) {
-            // ---- 1a. take this batch's picks from LDS as they appear, four slots per
-            //      read (the others are often there already) ----
-            const int batch_base = applied;
-            while (true) {
-                const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
-                u32x4 sl[4];
-                lds_read64(sl[0], sl[1], sl[2], sl[3], pk_off + pos * 16);
-                // every lane read the same slots: the sequence numbers are wave-uniform
-                if (__builtin_amdgcn_readfirstlane((int)sl[0].w) == applied) {
+        int applied = 0;  // picks applied so far
+        for (;;) {
+            // ---- 1a. the picks of the round (first the seed point), which are all in
+            //      place by now: {round, picks so far} says how many.  Eight slots per
+            //      step; the slots behind the last pick of the round hold picks of
+            //      earlier rounds (or the seed point), which every value reflects
+            //      already, so applying those again changes nothing. ----
+            const u32x2 f = lds_read8(fin_off);
+            const int upto = __builtin_amdgcn_readfirstlane((int)f.y);
+            for (int c0 = 0; c0 < upto - applied; c0 += 8) {
+                u32x4 sl[8];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (__builtin_amdgcn_readfirstlane((int)sl[e].w) != applied) break;
-                        ++applied;
-                        const float lx = u2f(sl[e].x), ly = u2f(sl[e].y), lz = u2f(sl[e].z);
+                for (int e = 0; e < 8; ++e) sl[e] = L.pk[c0 + e];
 #pragma unroll
-                        for (int j = 0; j < P; ++j)
-                            m[j] = min_dist(m[j], sqdist(x[j], y[j], z[j], lx, ly, lz));
-                    }
-                } else {
-                    const u32x2 f = lds_read8(fin_off);
-                    if (__builtin_amdgcn_readfirstlane((int)f.x) == batch &&
-                        applied >= __builtin_amdgcn_readfirstlane((int)f.y))
-                        break;
-                    __builtin_amdgcn_s_sleep(1);
+                for (int e = 0; e < 8; ++e) {
+                    const float lx = u2f(sl[e].x), ly = u2f(sl[e].y), lz = u2f(sl[e].z);
+#pragma unroll
+                    for (int j = 0; j < P; ++j) m[j] = min_dist(m[j], sqdist(x[j], y[j], z[j], lx, ly, lz));
                 }
             }
+            applied = upto;
             if (s_abort || applied >= a.M) break;
             // ---- 1b. the lane's kT + 1 largest values (element numbers for the first kT) ----
             float top[kT + 1];
@@ -208,10 +201,11 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
                 }
             }
             __syncthreads();  // wave tops ready for the communication wave
-            // ---- 1d. help to rank the candidates of the next round ----
-            team_barrier();  // the communication wave has the keys in place
+            // ---- 1d. help with the replay of the next round ----
+            team_barrier();  // the communication wave has the candidates in place
             team_matrix(L, lane, wave, NWK + 1);
-            team_barrier();  // ranks complete
+            team_barrier();  // masks complete
+            team_barrier();  // picks of the round in place
         }
         return;
     }
@@ -285,8 +279,9 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
                 s_abort = 1;
                 u32x2 f;
                 f.x = round; f.y = 0u;
-                lds_write8(fin_off, f);  // releases the workers, which then see s_abort
+                lds_write8(fin_off, f);  // no new picks; the workers then see s_abort
             }
+            team_barrier();
             return;
         }
         // release the workers first, then note the picks (workgroup 0 only)
@@ -295,6 +290,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             f.x = round; f.y = (uint32_t)(npicked + cnt);
             lds_write8(fin_off, f);
         }
+        team_barrier();  // the workers wait here for the picks
         if (w == 0) record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
         npicked += cnt;
         FFPS_STAMP(prof, 4);
@@ -324,14 +320,15 @@ hipError_t launch_t(GridArgs &a, int num_wg, hipStream_t s) {
 }
 
 // Kernel shapes (worker waves, points per worker lane), ordered by capacity; a
-// workgroup's slice runs on the first shape that holds it.  Among shapes of
-// similar capacity the one with fewer points per lane and more waves does less
-// arithmetic per pick on its busiest SIMD.
-#define FFPS_GRID_SHAPES(X)                                                                     \
-    X(3, 1) X(3, 2) X(7, 1) X(3, 3) X(7, 2) X(7, 3) X(7, 4) X(15, 2) X(7, 5) X(15, 3) X(15, 4) \
-    X(15, 5) X(15, 6) X(15, 8) X(15, 10) X(15, 13)
+// workgroup's slice runs on the first shape that holds it.  At most eight waves
+// per workgroup: two per SIMD keep the arithmetic units busy, and with 256
+// registers per lane neither the worker waves (four registers per point) nor
+// the communication wave spill.
+#define FFPS_GRID_SHAPES(X)                                                                  \
+    X(3, 1) X(3, 2) X(7, 1) X(3, 3) X(7, 2) X(7, 3) X(7, 4) X(7, 5) X(7, 6) X(7, 8) X(7, 10) \
+    X(7, 12) X(7, 16) X(7, 20) X(7, 24) X(7, 28)
 
-constexpr int kMaxPointsPerWG = 12 * kWave * 16;  // 12288 <= 15 * 64 * 13
+constexpr int kMaxPointsPerWG = 12 * kWave * 16;  // 12288 <= 7 * 64 * 28
 
 // Worker waves of the shape that holds per_wg points (0 if none does).
 int shape_waves(int per_wg) {

@@ -155,7 +155,7 @@ def test_plan_of_the_five_configurations_and_its_limits():
         for N in (4609, 9000, 12500, 16384, 50000, 100000, 786433, 3000000):
             k, g, u, c = plan(B, N, GRID)
             assert k == GRID and 1 <= g <= 256 and 1 <= c <= B and g * c <= 256
-            assert g <= u <= 256 and u % g == 0 and u // g in (1, 3, 7, 15)
+            assert g <= u <= 256 and u % g == 0 and u // g in (1, 3, 7)
             assert N <= g * 12288                      # every workgroup's slice fits its registers
     # a smaller device gets fewer workgroups, never more units than the exchange area holds
     k, g, u, c = plan(1, 200000, GRID, 64)
