@@ -16,10 +16,12 @@ minimum distances stay in registers for the whole call, so no memory system
 bounds it; what the hardware limits is the fp32 vector arithmetic of the
 updates themselves.  An update is 3 subtractions, 3 multiplications, 2
 additions and 1 minimum, each individually rounded: 9 operations that can
-neither be fused (the method fixes the rounding) nor packed two to an
-instruction (the build rules them out).  Peak for such code = 256 CUs x 4 SIMDs
-x 16 lanes x 2.4 GHz = 39.3 T operations/s (a quarter of the published 157.3
-TFLOP/s, which counts a packed fused multiply-add as four).
+not be fused (the method fixes the rounding of each).  Peak for such code = half
+the published 157.3 TFLOP/s fp32 vector rate, which counts a fused multiply-add
+as two: 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6 T operations/s.
+The rate that plain, unfused and unpacked fp32 instructions sustain on the
+device is measured in the same run (`alu_probe`, the library's diagnostic
+kernel) and reported beside it.
 The HBM-equivalent rate (20 B per update over the same time: what a streaming
 loop would have to move) is reported as an extra key, not as a roofline.
 
@@ -38,11 +40,11 @@ sys.path.insert(0, ROOT)
 
 N, STAGES = 200000, (50000, 12500, 3125, 781)
 KEEP = (1, 4)
-OPS_PER_UPDATE = 9             # 3 sub + 3 mul + 2 add + 1 min, none fused, none packed
+OPS_PER_UPDATE = 9             # 3 sub + 3 mul + 2 add + 1 min, none fused
 BYTES_PER_UPDATE = 20          # xyz 12 B + min-distance read 4 B + write 4 B
 HBM_PEAK_GBS = 8000.0
-MI355X_CUS, MI355X_GHZ, SIMDS_PER_CU, LANES_PER_SIMD_CLOCK = 256, 2.4, 4, 16
-ALU_PEAK_TOPS = MI355X_CUS * SIMDS_PER_CU * LANES_PER_SIMD_CLOCK * MI355X_GHZ / 1e3   # 39.3
+MI355X_CUS, MI355X_GHZ, SIMDS_PER_CU, LANES_PER_SIMD_CLOCK = 256, 2.4, 4, 32
+ALU_PEAK_TOPS = MI355X_CUS * SIMDS_PER_CU * LANES_PER_SIMD_CLOCK * MI355X_GHZ / 1e3   # 78.6
 
 
 def updates_of_chain(sizes):
@@ -185,9 +187,9 @@ def main():
                                f"{plan[2]} reporting units)",
                      "ops_per_update": OPS_PER_UPDATE,
                      "algorithmic_ops_per_launch": upd_exact * OPS_PER_UPDATE,
-                     "peak_derivation": "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one individually "
-                                        "rounded fp32 operation per lane and clock (no FMA: the method "
-                                        "fixes the rounding; no packed fp32: ruled out by the build)",
+                     "peak_derivation": "256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz = half the "
+                                        "published 157.3 TFLOP/s, which counts a fused multiply-add as two "
+                                        "(the method fixes the rounding of every operation, so none is fused)",
                      "note": "points and minimum distances stay in registers; `traffic` is what the "
                              "hardware counters saw for one launch (exchange records), from the "
                              "committed profile"},
@@ -201,6 +203,11 @@ def main():
         # mix into the profiler's average for the dominant kernel; the cost of a round
         # does not depend on the number of points per workgroup.
         result["grid_barrier_us"] = fb.ffps_barrier_probe(20000, workspace=ws)
+        # what plain fp32 vector instructions sustain on this device (no memory traffic)
+        result["alu_probe"] = {"unit": "T operations/s", "operations": "sub, mul, add, min on 16 values per lane",
+                               "by_waves_per_cu": {str(wv): fb.ffps_alu_probe(wv, 20000, workspace=ws) / 1e12
+                                                   for wv in (4, 8, 16, 32)}}
+        result["roofline"]["sustained_by_plain_fp32"] = max(result["alu_probe"]["by_waves_per_cu"].values())
         n_one, m_one = 100000, 4001
         x_one = x[:, :n_one].contiguous()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -237,6 +237,21 @@ int ffps_describe_plan(int B, int N, int variant, int num_cu, int *kernel, int *
  */
 int ffps_barrier_probe(int iters, void *d_ws, size_t ws_bytes, void *stream, float *us_per_barrier);
 
+/*
+ * Diagnostic for benchmarks, not part of the sampling path: the sustained rate
+ * of individually rounded fp32 vector operations (subtract, multiply, add,
+ * minimum: the arithmetic of one distance update of Eq. 1, no FMA, no memory
+ * traffic) with waves_per_cu waves of 64 lanes resident on every compute unit
+ * (1 .. 32), each lane working on 16 independent values for `iters` rounds.
+ * Creates two events, launches two kernels and waits for them.
+ *   d_ws / ws_bytes  a workspace of at least ffps_workspace_bytes(1, 1, 1); its
+ *                    exchange area takes one word per wave
+ *   ops_per_s        out (host): operations per second over all lanes
+ * Returns FFPS_OK or FFPS_ERR_INVALID_ARG / WORKSPACE_TOO_SMALL / LAUNCH_FAILED.
+ */
+int ffps_alu_probe(int waves_per_cu, int iters, void *d_ws, size_t ws_bytes, void *stream,
+                   double *ops_per_s);
+
 #ifdef __cplusplus
 }
 #endif

@@ -37,7 +37,7 @@ def variant_with_picks(variant: int, picks: int) -> int:
 
 EXPORTS = ["ffps_version", "ffps_strerror", "ffps_prune_sizes", "ffps_workspace_bytes",
            "ffps_exact", "ffps_prune", "ffps_cached_stages", "ffps_last_status",
-           "ffps_last_rounds", "ffps_barrier_probe", "ffps_gather_rows", "ffps_describe_plan",
+           "ffps_last_rounds", "ffps_barrier_probe", "ffps_alu_probe", "ffps_gather_rows", "ffps_describe_plan",
            "ffps_exact_noalloc"]
 
 
@@ -76,6 +76,7 @@ def lib() -> ctypes.CDLL:
         L.ffps_last_rounds.argtypes = [c_vp, c_vp]
         L.ffps_gather_rows.argtypes = [c_vp, c_int, c_int, c_int, c_vp, ctypes.c_long, c_int, c_vp, c_vp]
         L.ffps_barrier_probe.argtypes = [c_int, c_vp, c_sz, c_vp, ctypes.POINTER(ctypes.c_float)]
+        L.ffps_alu_probe.argtypes = [c_int, c_int, c_vp, c_sz, c_vp, ctypes.POINTER(ctypes.c_double)]
         L.ffps_describe_plan.argtypes = [c_int, c_int, c_int, c_int, ip, ip, ip, ip]
         for n in EXPORTS:
             if n not in ("ffps_strerror",):
@@ -249,6 +250,18 @@ def ffps_last_status(workspace, stream=None) -> int:
 def ffps_last_rounds(workspace, stream=None) -> int:
     torch = _torch()
     return lib().ffps_last_rounds(workspace.data_ptr(), _stream(torch, stream))
+
+
+def ffps_alu_probe(waves_per_cu, iters, workspace=None, stream=None) -> float:
+    """Sustained individually rounded fp32 vector operations per second (diagnostic)."""
+    torch = _torch()
+    ws = workspace if workspace is not None else make_workspace(1, 1, 1, stream=stream)
+    out = ctypes.c_double(0.0)
+    rc = lib().ffps_alu_probe(int(waves_per_cu), int(iters), ws.data_ptr(), ws.numel(), _stream(torch, stream),
+                              ctypes.byref(out))
+    if rc != 0:
+        raise FlashFPSError(rc, "ffps_alu_probe")
+    return out.value
 
 
 def ffps_barrier_probe(iters, workspace=None, stream=None) -> float:

@@ -467,6 +467,40 @@ int ffps_barrier_probe(int iters, void *d_ws, size_t ws_bytes, void *stream, flo
     return st;
 }
 
+int ffps_alu_probe(int waves_per_cu, int iters, void *d_ws, size_t ws_bytes, void *stream,
+                   double *ops_per_s) {
+    if (!d_ws || !ops_per_s || iters < 1 || iters > (1 << 20) || waves_per_cu < 1 || waves_per_cu > 32)
+        return FFPS_ERR_INVALID_ARG;
+    Workspace w = carve(1, 1, 1);
+    if (ws_bytes < w.total) return FFPS_ERR_WORKSPACE_TOO_SMALL;
+    Device dev = query_device();
+    if (dev.ok) return dev.ok;
+    hipStream_t s = (hipStream_t)stream;
+    // up to 16 waves in a workgroup; more waves per CU as two workgroups per CU
+    const int per_wg = waves_per_cu > 16 ? (waves_per_cu + 1) / 2 : waves_per_cu;
+    const int num_wg = dev.num_cu * (waves_per_cu > 16 ? 2 : 1);
+    if ((size_t)num_wg * per_wg * sizeof(float) > kExchangeBytesPerCloud) return FFPS_ERR_INVALID_ARG;
+    float *sink = (float *)((char *)d_ws + w.exchange);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+        return FFPS_ERR_LAUNCH_FAILED;
+    int rc = FFPS_OK;
+    hipError_t e = launch_alu_probe(sink, num_wg, per_wg, 16, s);  // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    if (e == hipSuccess) e = launch_alu_probe(sink, num_wg, per_wg, iters, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    float ms = 0.f;
+    if (e != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+        rc = FFPS_ERR_LAUNCH_FAILED;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    // 16 values x 4 operations per lane and iteration
+    *ops_per_s = (double)num_wg * per_wg * 64.0 * 16.0 * 4.0 * (double)iters / ((double)ms * 1e-3);
+    return FFPS_OK;
+}
+
 int ffps_last_rounds(const void *d_ws, void *stream) {
     if (!d_ws) return FFPS_ERR_INVALID_ARG;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;

@@ -334,6 +334,37 @@ inline int wrap_point(int N, int Nc, int start) {
 
 }  // namespace
 
+// Diagnostic: sustained rate of the arithmetic of a distance update.  Every lane
+// keeps 16 independent values and applies subtract, multiply, add, minimum to
+// each of them `iters` times: individually rounded fp32 operations with no
+// memory traffic, the mix of Eq. 1's inner loop.  One word per wave goes to
+// `sink` so that the work cannot be dropped.
+__global__ __launch_bounds__(1024) void k_alu_probe(int iters, float seed, float *sink) {
+    constexpr int CH = 16;
+    float a[CH];
+    const float b = seed + (float)threadIdx.x * 1e-3f, c = 0.999f;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) a[i] = (float)(i + (int)threadIdx.x);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            a[i] = __fsub_rn(a[i], b);
+            a[i] = __fmul_rn(a[i], c);
+            a[i] = __fadd_rn(a[i], b);
+            a[i] = fminf(a[i], 1e30f);
+        }
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) t += a[i];
+    if ((threadIdx.x & 63) == 0) sink[(blockIdx.x * blockDim.x + threadIdx.x) >> 6] = t;
+}
+
+hipError_t launch_alu_probe(float *sink, int num_wg, int waves_per_wg, int iters, hipStream_t s) {
+    k_alu_probe<<<dim3(num_wg), dim3(64 * waves_per_wg), 0, s>>>(iters, 1.0f, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_barrier_probe(unsigned *counter, int *status, int num_wg, int iters, hipStream_t s) {
     void *params[] = {&counter, &iters, &status};
     return hipLaunchCooperativeKernel((const void *)k_barrier_probe, dim3(num_wg), dim3(256), params,

@@ -320,13 +320,14 @@ hipError_t launch_t(GridArgs &a, int num_wg, hipStream_t s) {
 }
 
 // Kernel shapes (worker waves, points per worker lane), ordered by capacity; a
-// workgroup's slice runs on the first shape that holds it.  At most eight waves
-// per workgroup: two per SIMD keep the arithmetic units busy, and with 256
-// registers per lane neither the worker waves (four registers per point) nor
-// the communication wave spill.
-#define FFPS_GRID_SHAPES(X)                                                                  \
-    X(3, 1) X(3, 2) X(7, 1) X(3, 3) X(7, 2) X(7, 3) X(7, 4) X(7, 5) X(7, 6) X(7, 8) X(7, 10) \
-    X(7, 12) X(7, 16) X(7, 20) X(7, 24) X(7, 28)
+// workgroup's slice runs on the first shape that holds it.  Eight waves per
+// workgroup: two per SIMD issue plain fp32 instructions at nearly twice the rate
+// of one, all eight share the pairwise work of a round, and with 256 registers
+// per lane neither the worker waves (four registers per point) nor the
+// communication wave spill.
+#define FFPS_GRID_SHAPES(X)                                                               \
+    X(7, 1) X(7, 2) X(7, 3) X(7, 4) X(7, 5) X(7, 6) X(7, 8) X(7, 10) X(7, 12) X(7, 16) X(7, 20) \
+    X(7, 24) X(7, 28)
 
 constexpr int kMaxPointsPerWG = 12 * kWave * 16;  // 12288 <= 7 * 64 * 28
 

@@ -59,6 +59,7 @@ hipError_t launch_fps_stream(const float *xyz, float *mind, int N, int M, int st
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 // `iters` grid barriers over num_wg co-resident workgroups; *counter must be zero
 hipError_t launch_barrier_probe(unsigned *counter, int *status, int num_wg, int iters, hipStream_t s);
+hipError_t launch_alu_probe(float *sink, int num_wg, int waves_per_wg, int iters, hipStream_t s);
 // cxyz[b][i] = xyz[b][cand(i)], cand = the sorted strided candidate list (see flashfps.h)
 hipError_t launch_gather_candidates(const float *xyz, int B, int N, int Nc, int start,
                                     float *cxyz, hipStream_t s);

@@ -11,7 +11,7 @@ print Markdown; the summaries under profiles/ are their output.
       phases of every round with the 100 MHz wall clock and counts shader
       cycles inside the replay loops).
 
-    python -m paper_2604_17720_amd.profiling summarize --stats S.csv [--fetch F.csv --write W.csv]
+    python -m paper_2604_17720_amd.profiling summarize [--stats S.csv] [--trace T.csv] [--fetch F.csv --write W.csv]
 
       Tables from rocprofv3's CSV output: per-kernel time (--kernel-trace
       --stats) and HBM bytes per dispatch (--pmc FETCH_SIZE / --pmc WRITE_SIZE,
@@ -98,6 +98,22 @@ def _summarize(args) -> None:
                   f"{float(r['AverageNs']) / 1e3:.1f} | {float(r['Percentage']):.2f} | "
                   f"{int(r['MinNs']) / 1e3:.1f} | {int(r['MaxNs']) / 1e3:.1f} |")
         print()
+    if args.trace:
+        # per kernel AND launch size: one instantiation serves clouds of several sizes
+        d = collections.OrderedDict()
+        for r in csv.DictReader(open(args.trace)):
+            key = (_short(r["Kernel_Name"])[:70], int(r["Grid_Size_X"]) // max(int(r["Workgroup_Size_X"]), 1),
+                   r["Workgroup_Size_X"])
+            d.setdefault(key, []).append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+        total = sum(sum(v) for v in d.values())
+        print("| kernel | workgroups x threads | calls | total ms | average us | % | min us | max us |")
+        print("|---|---|---|---|---|---|---|---|")
+        for k, v in sorted(d.items(), key=lambda kv: -sum(kv[1])):
+            if sum(v) / total < 0.0005:
+                continue
+            print(f"| `{k[0]}` | {k[1]} x {k[2]} | {len(v)} | {sum(v) / 1e3:.3f} | {sum(v) / len(v):.1f} | "
+                  f"{100 * sum(v) / total:.2f} | {min(v):.1f} | {max(v):.1f} |")
+        print()
     if not (args.fetch and args.write):
         return
 
@@ -150,6 +166,7 @@ def main(argv=None) -> None:
     sub.add_parser("phases")
     s = sub.add_parser("summarize")
     s.add_argument("--stats")
+    s.add_argument("--trace", help="kernel trace CSV: table per kernel and launch size")
     s.add_argument("--fetch")
     s.add_argument("--write")
     s.add_argument("--kernel", help="kernel whose per-launch traffic is printed as `traffic_bytes_per_launch:`")

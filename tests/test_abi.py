@@ -125,7 +125,7 @@ def test_plan_of_the_five_configurations_and_its_limits():
     plan = fb.ffps_describe_plan
     assert plan(1, 1024) == (WG, 1, 192, 1)            # config 1: one unit per worker lane
     assert plan(32, 1024) == (WG, 1, 192, 32)          # config 2
-    assert plan(8, 16384) == (GRID, 28, 196, 8)        # config 3: 28 workgroups x 7 reporting waves
+    assert plan(8, 16384) == (GRID, 32, 224, 8)        # config 3: 32 workgroups x 7 reporting waves
     assert plan(1, 200000) == (GRID, 256, 256, 1)      # config 4: one unit per workgroup
     assert plan(1, 300000) == (GRID, 256, 256, 1)      # config 5
     # the boundaries of the kernels
@@ -155,7 +155,7 @@ def test_plan_of_the_five_configurations_and_its_limits():
         for N in (4609, 9000, 12500, 16384, 50000, 100000, 786433, 3000000):
             k, g, u, c = plan(B, N, GRID)
             assert k == GRID and 1 <= g <= 256 and 1 <= c <= B and g * c <= 256
-            assert g <= u <= 256 and u % g == 0 and u // g in (1, 3, 7)
+            assert g <= u <= 256 and u % g == 0 and u // g in (1, 7)
             assert N <= g * 12288                      # every workgroup's slice fits its registers
     # a smaller device gets fewer workgroups, never more units than the exchange area holds
     k, g, u, c = plan(1, 200000, GRID, 64)

@@ -74,11 +74,11 @@ def test_config3_medium_clouds(fb, oracle, variant):
 
 @pytest.mark.parametrize("variant", [0, GRID])
 def test_config3_full_batch(fb, oracle, variant):
-    """B = 8 clouds of 16,384 points: eight clusters of 28 workgroups, seven
+    """B = 8 clouds of 16,384 points: eight clusters of 32 workgroups, seven
     reporting waves each, in one launch."""
     x = inputs.make_config(3)
     assert x.shape == (8, 16384, 3)
-    assert fb.ffps_describe_plan(8, 16384, variant, 256) == (GRID, 28, 196, 8)
+    assert fb.ffps_describe_plan(8, 16384, variant, 256) == (GRID, 32, 224, 8)
     _check_exact(fb, oracle, x, 4096, 0, variant)
 
 
