@@ -568,12 +568,15 @@ __device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const 
 // With TEAM the other waves of the workgroup take part in the replay: they
 // wait at a workgroup barrier after handing in their reports, call team_matrix
 // and pass a second barrier, every round; this function passes the same two
-// barriers exactly once, whatever path the round takes.
+// barriers exactly once, whatever path the round takes.  live_sets (1 .. kSets)
+// limits the live candidates to that many per lane: the pairwise work grows with
+// the square of their number, and where a round ends after a few tens of picks
+// anyway (small clouds) the candidates further down the order are not reached.
 template <int KC, bool TEAM = false>
 __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint32_t (&cv)[KC],
                                             uint32_t (&ci)[KC], float (&cx)[KC], float (&cy)[KC],
                                             float (&cz)[KC], uint32_t lb, int npicked, int cap,
-                                            RoundProf *prof, int team_waves = 1) {
+                                            RoundProf *prof, int team_waves = 1, int live_sets = kSets) {
     const uint32_t pk_off = lds_offset(L.pk);
 #ifdef FFPS_PROFILE
     uint64_t sc = clock64();
@@ -663,8 +666,8 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             }
         };
         count_live();
-        if (total > kMaxLive) {
-            // the largest value that is only number kSets + 1 in its lane
+        if (total > live_sets * kWave) {
+            // the largest value that is only number live_sets + 1 in its lane
             uint32_t t[kSets + 1] = {};
 #pragma unroll
             for (int q = 0; q < KC; ++q) {
@@ -673,7 +676,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 for (int r = kSets; r >= 1; --r) t[r] = umax(t[r], v < t[r - 1] ? v : t[r - 1]);
                 t[0] = umax(t[0], v);
             }
-            T = umax(Bound, wave_max_u32(t[kSets]));
+            T = umax(Bound, wave_max_u32(live_sets == 1 ? t[1] : live_sets == 2 ? t[2] : t[kSets]));
             count_live();
         }
     }
@@ -771,13 +774,12 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             //      other waves work out, for every pair of live candidates, which one
             //      comes first and what picking it does to the other (team_matrix).
             //      Candidate b is a pick of this round when no pick before it lowers
-            //      it; it is out of the round when a pick before it lowers it to the
-            //      threshold or below; otherwise a pick lowers it to a value that is
-            //      still live, and the round ends before it.  Which candidates are
-            //      picks follows from the candidates before them alone, so starting
-            //      from "all of them" and applying the rule to every candidate at once
-            //      settles one more candidate of the order per pass at least, and in
-            //      practice all of them after a few passes. ----
+            //      it.  Which candidates are picks follows from the candidates before
+            //      them alone, so starting from "all of them" and applying the rule to
+            //      every candidate at once settles one more candidate of the order per
+            //      pass at least, and in practice all of them after a few passes.
+            //      What becomes of the lowered candidates, and where the round ends
+            //      because of them, is worked out afterwards (further down). ----
             if (lane < 16) {
                 // entries of value 0 behind the last candidate: they come after every
                 // live one, which keeps their bits out of the masks
@@ -841,7 +843,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                     uint32_t Q[NW];
 #pragma unroll
                     for (int s = 0; s < NS; ++s) {
-                        pk[s] = h[s] && !hits(KB[s], P);
+                        pk[s] = h[s] && !hits(LB[s], P);
                         pm[s] = __builtin_amdgcn_ballot_w64(pk[s]);
                     }
                     to_words(pm, Q);
@@ -853,23 +855,47 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                     }
                     if (same) break;
                 }
-                // the round ends before the first candidate that a pick lowers without
-                // putting it out of the round
+                // A candidate that a pick lowers is not a pick of this round.  If the pick
+                // takes it to the threshold or below it is simply out of the round.
+                // Otherwise it is still live at a lower value, and it would be the next
+                // pick as soon as the candidates left in the order are no higher than
+                // that value: its new value is the smallest distance to the picks before
+                // it that lower it (few, and named by its mask), the largest such value
+                // over all lowered candidates is where the round ends, and the picks are
+                // the candidates strictly above it.
                 bool wounded[NS];
-                uint64_t wm[NS], any_w = 0;
-                uint32_t Wd[NW], F[NW];
+                uint64_t any_w = 0;
+                uint32_t F[NW];
 #pragma unroll
                 for (int s = 0; s < NS; ++s) {
-                    wounded[s] = pk[s] && hits(LB[s], P);
-                    wm[s] = __builtin_amdgcn_ballot_w64(wounded[s]);
-                    any_w |= wm[s];
+                    wounded[s] = h[s] && !pk[s] && !hits(KB[s], P);
+                    any_w |= __builtin_amdgcn_ballot_w64(wounded[s]);
                 }
                 ended = any_w != 0;
                 if (ended) {
-                    to_words(wm, Wd);
+                    uint32_t vstar = 0u;
 #pragma unroll
                     for (int s = 0; s < NS; ++s) {
-                        pk[s] = pk[s] && !wounded[s] && !hits(BB[s], Wd);
+                        uint32_t vp = 0xffffffffu;
+                        const float xb = u2f(c[s].x), yb = u2f(c[s].y), zb = u2f(c[s].z);
+#pragma unroll
+                        for (int wd = 0; wd < NW; ++wd) {
+                            uint32_t m = wounded[s] ? (LB[s][wd] & P[wd]) : 0u;
+                            while (__builtin_amdgcn_ballot_w64(m != 0u) != 0) {
+                                const bool act = m != 0u;
+                                const int lz = __builtin_clz(m | 1u);  // the first candidate left in the word
+                                m &= ~(0x80000000u >> lz);
+                                const u32x4 ra = lds_read16(cand_off + (act ? (uint32_t)(wd * 32 + lz) : 0u) * 16);
+                                const uint32_t d = f2u(sqdist(xb, yb, zb, u2f(ra.x), u2f(ra.y), u2f(ra.z)));
+                                vp = act && d < vp ? d : vp;
+                            }
+                        }
+                        vstar = umax(vstar, wounded[s] ? vp : 0u);
+                    }
+                    vstar = wave_max_u32(vstar);
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) {
+                        pk[s] = pk[s] && o[s] > vstar;
                         pm[s] = __builtin_amdgcn_ballot_w64(pk[s]);
                     }
                 }

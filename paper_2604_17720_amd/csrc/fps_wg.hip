@@ -127,18 +127,17 @@ static hipError_t launch_wg_t(const float *xyz, int B, int N, int M, int start, 
 // ---------------------------------------------------------------------------
 // k_fps_wgm: one workgroup per cloud, MANY picks per pass over the points.
 //
-// The workgroup is one REPLAY wave (wave 0) plus NWK worker waves that own the
-// points (point i belongs to worker lane i mod NTW); waves 4, 8, 12 exit at
-// once so that the replay wave has its SIMD to itself.  Per round every worker
+// The workgroup is one REPLAY wave (wave 0) plus seven worker waves that own the
+// points (point i belongs to worker lane i mod NTW).  Per round every worker
 // lane reports the two best of its own points and the value of its third best
 // (one 16-byte LDS record); the replay wave takes the 2 * NTW reported points as
-// candidates and replays the greedy rule of Eq. 1 on them alone (fps_exchange.h)
-// for as long as the best candidate stays strictly above every lane's
-// third-best value, since no unreported point can then be the maximum.  Picks
-// go to the workers through LDS one by one while the replay is still running.
-// A round delivers some tens of picks, so nothing is reduced over the whole
-// workgroup per pick: the lanes' reports need no cross-lane step at all, and
-// the replay runs inside one wave.
+// candidates and, together with the worker waves, replays the greedy rule of
+// Eq. 1 on them alone (fps_exchange.h) for as long as the best candidate stays
+// strictly above every lane's third-best value, since no unreported point can
+// then be the maximum.  The picks of a round go to the workers through LDS
+// together.  A round delivers some tens of picks, so nothing is reduced over
+// the whole workgroup per pick: the lanes' reports need no cross-lane step at
+// all.
 struct WgmArgs {
     const float *xyz;
     int N, M, start;
@@ -151,11 +150,11 @@ struct WgmArgs {
     int *status;  // status[1] receives the largest number of rounds any cloud took
 };
 
-__host__ __device__ constexpr int wgm_waves(int nwk) { return nwk + nwk / 3; }
+__host__ __device__ constexpr int wgm_waves(int nwk) { return nwk + 1; }
 
 template <int NWK, int P>
 __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
-    static_assert(NWK % 3 == 0 && NWK >= 3 && NWK <= 6, "worker waves come in threes");
+    static_assert(NWK == 7, "eight waves in all: two per SIMD");
     constexpr int NTW = NWK * kWave;  // worker lanes = reporting units
     constexpr int KR = NWK;           // records per lane of the replay wave
     constexpr int KC = 2 * KR;        // candidates per lane of the replay wave
@@ -173,7 +172,6 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
-    if (wave != 0 && (wave & 3) == 0) return;  // leaves the replay wave's SIMD to it
 
     const uint32_t pk_off = lds_offset(L.pk);
     const uint32_t fin_off = lds_offset(fin);
@@ -199,8 +197,8 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
 
     if (wave != 0) {
         // =============================== worker ===============================
-        const int wk = wave - 1 - wave / 4;  // 0 .. NWK-1
-        const int t = wk * kWave + lane;      // worker lane number
+        const int wk = wave - 1;          // 0 .. NWK-1
+        const int t = wk * kWave + lane;  // worker lane number
         // element j of this lane is point j * NTW + t: ascending in j
         float x[P], y[P], z[P], m[P];
 #pragma unroll
@@ -215,34 +213,26 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
             sxyz[i] = make_float4(x[j], y[j], z[j], 0.f);
         }
         __syncthreads();  // pick slots and coordinates in place
-        int applied = 0;  // picks applied so far = sequence number of the next pick
-        for (int batch = 0;; ++batch) {
-            // ---- take this batch's picks from LDS as they appear, four slots per read
-            //      (the others are often there already) ----
-            const int batch_base = applied;
-            while (true) {
-                const int pos = min(applied - batch_base, kMaxPicksPerRound - 1);
-                u32x4 sl[4];
-                lds_read64(sl[0], sl[1], sl[2], sl[3], pk_off + pos * 16);
-                // every lane read the same slots: the sequence numbers are wave-uniform
-                if (__builtin_amdgcn_readfirstlane((int)sl[0].w) == applied) {
+        int applied = 0;  // picks applied so far
+        for (;;) {
+            // ---- the picks of the round (first the seed point), which are all in place
+            //      by now: {round, picks so far} says how many.  Eight slots per step;
+            //      the slots behind the last pick of the round hold picks of earlier
+            //      rounds (or the seed point), which every value reflects already. ----
+            const u32x2 f = lds_read8(fin_off);
+            const int upto = __builtin_amdgcn_readfirstlane((int)f.y);
+            for (int c0 = 0; c0 < upto - applied; c0 += 8) {
+                u32x4 sl[8];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (__builtin_amdgcn_readfirstlane((int)sl[e].w) != applied) break;
-                        ++applied;
-                        const float lx = u2f(sl[e].x), ly = u2f(sl[e].y), lz = u2f(sl[e].z);
+                for (int e = 0; e < 8; ++e) sl[e] = L.pk[c0 + e];
 #pragma unroll
-                        for (int j = 0; j < P; ++j)
-                            m[j] = min_dist(m[j], sqdist(x[j], y[j], z[j], lx, ly, lz));
-                    }
-                } else {
-                    const u32x2 f = lds_read8(fin_off);
-                    if (__builtin_amdgcn_readfirstlane((int)f.x) == batch &&
-                        applied >= __builtin_amdgcn_readfirstlane((int)f.y))
-                        break;
-                    __builtin_amdgcn_s_sleep(1);
+                for (int e = 0; e < 8; ++e) {
+                    const float lx = u2f(sl[e].x), ly = u2f(sl[e].y), lz = u2f(sl[e].z);
+#pragma unroll
+                    for (int j = 0; j < P; ++j) m[j] = min_dist(m[j], sqdist(x[j], y[j], z[j], lx, ly, lz));
                 }
             }
+            applied = upto;
             if (applied >= a.M) break;
             // ---- the lane's top three values (element numbers for the first two) ----
             float a1 = m[0], a2 = 0.f, a3 = 0.f;
@@ -262,12 +252,16 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
             r.w = (uint32_t)j1 | ((uint32_t)j2 << 16);
             rec[t] = r;
             __syncthreads();  // records ready for the replay wave
+            team_barrier();   // which has the candidates in place
+            team_matrix(L, lane, wave, NWK + 1);
+            team_barrier();   // masks complete
+            team_barrier();   // picks of the round in place
         }
         return;
     }
 
     // ============================== replay wave ==============================
-    __syncthreads();  // coordinates in place
+    team_barrier();  // coordinates and pick slots in place
     int npicked = 1;
     int round = 0;
     RoundProf *prof = nullptr;
@@ -301,13 +295,15 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
         }
         const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
         FFPS_STAMP(prof, 2);
-        const RoundResult res = replay_round<KC>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof);
+        const RoundResult res = replay_round<KC, true>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof,
+                                                       NWK + 1);
         // release the workers first, then note the picks
         if (lane == 0) {
             u32x2 f;
             f.x = (uint32_t)round; f.y = (uint32_t)(npicked + res.cnt);
             lds_write8(fin_off, f);
         }
+        team_barrier();  // the workers wait here for the picks
         record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
         npicked += res.cnt;
         FFPS_STAMP(prof, 4);
@@ -334,11 +330,11 @@ static hipError_t launch_wgm_t(const WgmArgs &a, int B, hipStream_t s) {
 
 int wg_capacity() { return 1024 * 24; }
 
-int wgm_capacity() { return 6 * kWave * 12; }
+int wgm_capacity() { return 4608; }  // <= 7 * 64 * 11
 
 int wg_units(int N) {
     if (N <= 64 * 4 || N > wgm_capacity()) return 0;
-    return N <= 3 * kWave * 6 ? 3 * kWave : 6 * kWave;  // one reporting unit per worker lane
+    return 7 * kWave;  // one reporting unit per worker lane
 }
 
 // Very small clouds (one wave holds them) and clouds beyond the multi-pick
@@ -361,14 +357,13 @@ hipError_t launch_fps_wg(const float *xyz, int B, int N, int M, int start, const
                                     : (max_picks > kMaxPicksPerRound ? kMaxPicksPerRound : max_picks);
 #define FFPS_WGM_CASE(NWK, P) \
     if (N <= (NWK) * kWave * (P)) return launch_wgm_t<NWK, P>(a, B, s);
-        // one worker wave per SIMD up to 1152 points, two beyond
-        FFPS_WGM_CASE(3, 2)
-        FFPS_WGM_CASE(3, 4)
-        FFPS_WGM_CASE(3, 6)
-        FFPS_WGM_CASE(6, 4)
-        FFPS_WGM_CASE(6, 6)
-        FFPS_WGM_CASE(6, 8)
-        FFPS_WGM_CASE(6, 12)
+        FFPS_WGM_CASE(7, 1)
+        FFPS_WGM_CASE(7, 2)
+        FFPS_WGM_CASE(7, 3)
+        FFPS_WGM_CASE(7, 4)
+        FFPS_WGM_CASE(7, 6)
+        FFPS_WGM_CASE(7, 8)
+        FFPS_WGM_CASE(7, 11)
 #undef FFPS_WGM_CASE
     }
     FFPS_WG_CASE(1024, 8)

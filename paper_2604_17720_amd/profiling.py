@@ -9,7 +9,7 @@ print Markdown; the summaries under profiles/ are their output.
       inside the kernel by the profiling build (libflashfps_prof.so: the same
       sources with -DFFPS_PROFILE; workgroup 0's communication wave stamps the
       phases of every round with the 100 MHz wall clock and counts shader
-      cycles inside the replay loops).
+      cycles inside the replay).
 
     python -m paper_2604_17720_amd.profiling summarize [--stats S.csv] [--trace T.csv] [--fetch F.csv --write W.csv]
 
@@ -69,18 +69,15 @@ def _phases(args) -> None:
         print(f"| sum | {sum(st[8:13]) * 10.0 / r:.0f} |")
         print()
         print(f"- polls per gather: {st[15] / r:.2f}")
-        print(f"- replay set-up, shader cycles per round: bounds {st[24] / r:.0f}, counting {st[25] / r:.0f}, "
-              f"compaction {st[26] / r:.0f}, ordering {st[27] / r:.0f}")
-        if st[21] + st[23] > 0:
-            print(f"- pick loop: {st[20] / max(st[21], 1):.0f} cycles per pick over {st[21]} picks with one "
-                  f"candidate per lane, {st[22] / max(st[23], 1):.0f} over {st[23]} picks with more")
-        print(f"- inside the ordering, shader cycles per round: own load {st[32] / r:.0f}, first barrier "
-              f"{st[33] / r:.0f}, ranking share {st[34] / r:.0f}, second barrier {st[35] / r:.0f}, placing "
-              f"{st[36] / r:.0f}, rest {st[37] / r:.0f}")
-        print(f"- per round: {st[28] / r:.1f} live candidates, {st[29] / r:.1f} passed over, "
-              f"{st[30] / r:.2f} rounds ended early by a lowered candidate, {st[31] / r:.3f} exact re-orderings "
-              f"(three or more equal values in a row)")
-        print(f"- rounds by path: up to 64 live candidates {st[13]}, more {st[14]}, general {r - st[13] - st[14]}")
+        print(f"- inside the replay, shader cycles per round: bounds {st[24] / r:.0f}, counting {st[25] / r:.0f}, "
+              f"compaction {st[26] / r:.0f}, work of the whole workgroup {st[27] / r:.0f}")
+        print(f"- of which: own candidates back from LDS {st[32] / r:.0f}, first barrier {st[33] / r:.0f}, "
+              f"this wave's share of the pairwise masks {st[34] / r:.0f}, second barrier {st[35] / r:.0f}, "
+              f"settling the picks and handing them out {st[36] / r:.0f}")
+        print(f"- per round: {st[28] / r:.1f} live candidates, {(M - 1) / r:.1f} picks, "
+              f"{st[30] / r:.2f} rounds ended early by a lowered candidate")
+        print(f"- rounds by number of live candidates: up to 64: {st[13]}, 65 to {3 * 64}: {st[14]}, "
+              f"one pick at a time: {r - st[13] - st[14]}")
         print(f"- kernel: {st[16] * 0.01:.1f} us wall, {st[17] * 16 / (st[16] * 10.0):.3f} GHz shader clock\n")
 
 

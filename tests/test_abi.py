@@ -123,14 +123,14 @@ def test_plan_of_the_five_configurations_and_its_limits():
     import paper_2604_17720_amd.binding as fb
     WG, GRID, STREAM = fb.FFPS_VARIANT_WG, fb.FFPS_VARIANT_GRID, fb.FFPS_VARIANT_STREAM
     plan = fb.ffps_describe_plan
-    assert plan(1, 1024) == (WG, 1, 192, 1)            # config 1: one unit per worker lane
-    assert plan(32, 1024) == (WG, 1, 192, 32)          # config 2
+    assert plan(1, 1024) == (WG, 1, 448, 1)            # config 1: one unit per worker lane
+    assert plan(32, 1024) == (WG, 1, 448, 32)          # config 2
     assert plan(8, 16384) == (GRID, 32, 224, 8)        # config 3: 32 workgroups x 7 reporting waves
     assert plan(1, 200000) == (GRID, 256, 256, 1)      # config 4: one unit per workgroup
     assert plan(1, 300000) == (GRID, 256, 256, 1)      # config 5
     # the boundaries of the kernels
     assert plan(1, 256)[0] == WG and plan(1, 256)[2] == 0          # one-pick kernel, no rounds
-    assert plan(1, 257)[2] == 192 and plan(1, 1152)[2] == 192 and plan(1, 1153)[2] == 384
+    assert plan(1, 257)[2] == 448 and plan(1, 4608)[2] == 448
     assert plan(1, 4608)[0] == WG and plan(1, 4609)[0] == GRID
     assert plan(1, 256 * 12288)[0] == GRID and plan(1, 256 * 12288 + 1)[0] == STREAM
     assert plan(1, 1 << 25) == (STREAM, 256, 256, 1)
