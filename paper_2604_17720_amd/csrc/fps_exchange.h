@@ -572,11 +572,14 @@ __device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const 
 // limits the live candidates to that many per lane: the pairwise work grows with
 // the square of their number, and where a round ends after a few tens of picks
 // anyway (small clouds) the candidates further down the order are not reached.
+// live_target > 0 asks for about that many live candidates in all, for the same
+// reason.
 template <int KC, bool TEAM = false>
 __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint32_t (&cv)[KC],
                                             uint32_t (&ci)[KC], float (&cx)[KC], float (&cy)[KC],
                                             float (&cz)[KC], uint32_t lb, int npicked, int cap,
-                                            RoundProf *prof, int team_waves = 1, int live_sets = kSets) {
+                                            RoundProf *prof, int team_waves = 1, int live_sets = kSets,
+                                            int live_target = 0) {
     const uint32_t pk_off = lds_offset(L.pk);
 #ifdef FFPS_PROFILE
     uint64_t sc = clock64();
@@ -677,6 +680,13 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 t[0] = umax(t[0], v);
             }
             T = umax(Bound, wave_max_u32(live_sets == 1 ? t[1] : live_sets == 2 ? t[2] : t[kSets]));
+            count_live();
+        }
+        if (live_target > 0 && total > live_target + live_target / 4) {
+            // about live_target candidates, taking their values as evenly spread between
+            // the threshold and the best one (any threshold above the bound will do)
+            const uint32_t span = V - T;
+            T = V - (uint32_t)(((uint64_t)span * (uint32_t)live_target) / (uint32_t)total);
             count_live();
         }
     }
@@ -1218,7 +1228,8 @@ template <int T, bool TEAM = false>
 __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchange, int U, int unit0,
                                                       int nsub, int lane, uint32_t round,
                                                       const RoundInput<T> &in, int npicked, int cap,
-                                                      int *status, RoundProf *prof, int team_waves = 1) {
+                                                      int *status, RoundProf *prof, int team_waves = 1,
+                                                      int live_target = 0) {
     static_assert(T == 2 || T == 3, "two or three candidates per unit");
     constexpr int NCH = chunks_of(T);
     constexpr int KC = T * kRPL;  // candidates per lane before compaction
@@ -1310,7 +1321,8 @@ __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchang
         const uint32_t bnd = T == 2 ? r[0][q].z : r[NCH - 1][q].x;
         lb = umax(lb, present ? bnd : 0u);
     }
-    return replay_round<KC, TEAM>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof, team_waves);
+    return replay_round<KC, TEAM>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof, team_waves, kSets,
+                                  live_target);
 }
 
 }  // namespace ffps
