@@ -67,6 +67,12 @@ extern "C" {
  * points (1 = one pick per pass; 0 = library default).  The result never
  * depends on it. */
 #define FFPS_VARIANT_WITH_PICKS(variant, picks) ((variant) | ((picks) << 8))
+/* Test knob for the error path: a workgroup of the GRID kernel that does not find
+ * the records of all other workgroups at its first look gives up at once instead
+ * of after the library's bound on waiting.  Every workgroup then leaves the
+ * kernel in the ordinary way and the status word reads FFPS_ERR_TIMEOUT; the
+ * outputs of such a call are unspecified. */
+#define FFPS_VARIANT_TEST_NO_WAIT (1 << 16)
 
 /* Library version: major * 10000 + minor * 100 + patch.  Host only. */
 int ffps_version(void);

@@ -30,6 +30,9 @@ FFPS_VARIANT_STREAM = 3
 
 
 
+FFPS_VARIANT_TEST_NO_WAIT = 1 << 16
+
+
 def variant_with_picks(variant: int, picks: int) -> int:
     """FFPS_VARIANT_WITH_PICKS of the header."""
     return variant | (picks << 8)

@@ -120,7 +120,7 @@ inline int variant_picks(int variant) {
     return p == 0 ? kMaxPicksPerRound : p;
 }
 int check_variant(int variant) {
-    if (variant < 0 || (variant >> 16) != 0) return FFPS_ERR_INVALID_ARG;
+    if (variant < 0 || (variant >> 17) != 0) return FFPS_ERR_INVALID_ARG;
     int v = variant_kind(variant);
     return (v >= FFPS_VARIANT_AUTO && v <= FFPS_VARIANT_STREAM) ? FFPS_OK : FFPS_ERR_INVALID_ARG;
 }
@@ -175,7 +175,8 @@ int run_exact(const float *xyz, int B, int N, int M, int start, const int *start
                                            idx + b * idx_stride, idx_stride,
                                            md ? md + b * md_stride : nullptr, md_stride,
                                            ws + w.exchange, (int *)(ws + w.status),
-                                           plan.wg_per_cloud, variant_picks(variant), s);
+                                           plan.wg_per_cloud, variant_picks(variant),
+                                           (variant & FFPS_VARIANT_TEST_NO_WAIT) ? 0 : -1, s);
             if (e != hipSuccess) return FFPS_ERR_LAUNCH_FAILED;
         }
         return FFPS_OK;

@@ -1229,7 +1229,7 @@ __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchang
                                                       int nsub, int lane, uint32_t round,
                                                       const RoundInput<T> &in, int npicked, int cap,
                                                       int *status, RoundProf *prof, int team_waves = 1,
-                                                      int live_target = 0) {
+                                                      int live_target = 0, int spin_limit = kSpinLimit) {
     static_assert(T == 2 || T == 3, "two or three candidates per unit");
     constexpr int NCH = chunks_of(T);
     constexpr int KC = T * kRPL;  // candidates per lane before compaction
@@ -1271,7 +1271,7 @@ __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchang
         if (prof) ++prof->acc[7];
 #endif
         if (__builtin_amdgcn_ballot_w64(!all) == 0) break;
-        if (spin >= kSpinLimit) {
+        if (spin >= spin_limit) {
             gave_up = true;
             break;
         }

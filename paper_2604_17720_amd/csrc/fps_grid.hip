@@ -54,6 +54,7 @@ struct GridArgs {  // pointers are those of the first cloud of the launch
     char *exchange;    // per cloud: two buffers of buf_bytes(kT)
     int *status;
     int max_picks;
+    int spin_limit;    // polls a workgroup makes for the records of a round before it gives up
 };
 
 // Number of waves a workgroup with NWK worker waves launches: wave 0
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             in.bound = o.t.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
             res = exchange_round<kT, true>(L, a.exchange, G * NWK, w * NWK, NWK, lane, round, in, npicked,
-                                           cap, a.status, prof, NWK + 1);
+                                           cap, a.status, prof, NWK + 1, 0, a.spin_limit);
         } else {
             // ---- 2a. the workgroup's kT best + bound from the worker waves' ----
             const bool act = lane < NWK;
@@ -264,7 +265,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             in.bound = g3.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
             res = exchange_round<kT, true>(L, a.exchange, G, w, 1, lane, round, in, npicked, cap,
-                                           a.status, prof, NWK + 1);
+                                           a.status, prof, NWK + 1, 0, a.spin_limit);
         }
         const int cnt = res.cnt;
         if (cnt < 0) {
@@ -390,7 +391,7 @@ GridPlan plan_fps_grid(int B, int N, int num_cu) {
 hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start,
                            const int *start_dev, int32_t *idx, long idx_stride, float *md,
                            long md_stride, void *exchange, int *status, int wg_per_cloud,
-                           int max_picks, hipStream_t s) {
+                           int max_picks, int spin_limit, hipStream_t s) {
     const int G = wg_per_cloud;
     GridArgs a;
     a.xyz = xyz; a.N = N; a.M = M; a.start = start; a.start_dev = start_dev;
@@ -399,6 +400,7 @@ hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start
     a.md_out = md; a.md_stride = md_stride;
     a.exchange = (char *)exchange; a.status = status;
     a.max_picks = max_picks < 1 ? 1 : (max_picks > kMaxPicksPerRound ? kMaxPicksPerRound : max_picks);
+    a.spin_limit = spin_limit < 0 ? kSpinLimit : spin_limit;
     const int per_wg = (N + G - 1) / G;  // most points any workgroup holds
     const int num_wg = clouds * G;
     a.wave_units = units_of(N, G) > G ? 1 : 0;

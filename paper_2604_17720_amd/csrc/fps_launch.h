@@ -47,7 +47,7 @@ GridPlan plan_fps_grid(int B, int N, int num_cu);
 hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start,
                            const int *start_dev, int32_t *idx, long idx_stride, float *md,
                            long md_stride, void *exchange, int *status, int wg_per_cloud,
-                           int max_picks, hipStream_t s);
+                           int max_picks, int spin_limit, hipStream_t s);  // spin_limit < 0: the default
 
 // ---- fps_stream.hip: one cloud over the whole device, streamed from HBM ------
 // `mind` is an [N] fp32 scratch array; `exchange` and `status` as for the grid kernel.

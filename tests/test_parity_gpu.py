@@ -555,3 +555,20 @@ def test_config5_full_size(fb, oracle):
     rho = _radius64(x[0], p) / r_exact
     print("config 5 coverage ratio at p=75%:", rho, flush=True)
     assert 0.5 <= rho
+
+
+@pytest.mark.gpu
+def test_give_up_path_ends_cleanly_and_the_workspace_stays_usable(fb, oracle):
+    """FFPS_ERR_TIMEOUT, forced from the host: with the test knob a workgroup that
+    does not find every record at its first look gives up at once; all workgroups
+    then leave the kernel in the ordinary way, the status word reads
+    FFPS_ERR_TIMEOUT, and the next call on the same workspace is right again."""
+    x = inputs.make_config(4)[:, :60000].copy()
+    M = 1500
+    xd = _dev(x)
+    ws = fb.make_workspace(1, x.shape[1], M)
+    fb.ffps_exact(xd, M, 0, GRID | fb.FFPS_VARIANT_TEST_NO_WAIT, workspace=ws)
+    assert fb.ffps_last_status(ws) == fb.FFPS_ERR_TIMEOUT
+    got = fb.ffps_exact(xd, M, 0, GRID, workspace=ws)
+    assert fb.ffps_last_status(ws) == 0
+    assert np.array_equal(got.cpu().numpy(), oracle.fps_exact(x, M, 0))
