@@ -183,6 +183,9 @@ def main():
         "roofline": {"bound": "alu", "achieved": achieved_tops, "peak": ALU_PEAK_TOPS,
                      "unit": "TFLOP/s", "frac": achieved_tops / ALU_PEAK_TOPS,
                      "traffic": traffic, "traffic_source": traffic_src,
+                     "kernel_time_profile": "profiles/k_fps_grid_bench_config4_kernel_stats.md (this command "
+                                            "with --no-per-config: config 3's batch runs on the same "
+                                            "instantiation and launch size)",
                      "kernel": f"k_fps_grid (exact FPS, N={N}, M={M1}; {plan[1]} workgroups, "
                                f"{plan[2]} reporting units)",
                      "ops_per_update": OPS_PER_UPDATE,

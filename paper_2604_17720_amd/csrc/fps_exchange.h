@@ -1,26 +1,33 @@
-// Cross-workgroup exchange and candidate replay shared by the multi-workgroup
-// FPS kernels (register-resident and HBM-streaming).
+// The round shared by the multi-pick FPS kernels: cross-workgroup exchange of
+// candidate records and the replay of the greedy rule on them.
 //
-// The points of a cloud are divided among U <= 256 reporting UNITS (a whole
-// workgroup, or each worker wave of a workgroup).  Once per ROUND every unit
-// contributes its two best points and an upper bound on all its other points
-// (its third-best value).  One wave per workgroup publishes the records of its
-// units as four 16-byte chunks each, every chunk closed by a checksum that also
-// encodes the round, gathers the chunks of all U units with coalesced
+// The points of a cloud are divided among reporting UNITS (up to 256 across
+// workgroups: a whole workgroup, or each worker wave of a workgroup; or the
+// worker lanes of a single workgroup).  Once per ROUND every unit contributes
+// its T best points (two or three) and an upper bound on all its other points
+// (the next value).  Across workgroups one wave per workgroup publishes the
+// records of its units as 16-byte chunks, every chunk closed by a checksum that
+// also encodes the round, and gathers the chunks of all units with coalesced
 // device-scope loads (the only cross-workgroup step: no counters, no fences, no
-// separate barrier), and replays the greedy rule of Eq. 1 on the 2U published
-// candidates: the best candidate is the next pick as long as its value is
-// strictly above B = max of all bounds, because no unpublished point can then
-// reach it; picking it lowers the other candidates' values by the same distance
-// rule, and the replay continues until the test fails.  The first pick of a
-// round never needs the test: the global best point (largest value, lowest
-// index among equals) is the best of its own unit, hence published.
-// Every workgroup replays the same arithmetic on the same records, so all agree
-// on the picks without further communication.
+// separate barrier).  The greedy rule of Eq. 1 is then replayed on the
+// published candidates: the best candidate is the next pick as long as its
+// value is strictly above B = max of all bounds, because no unpublished point
+// can then reach it; picking it lowers the other candidates' values by the same
+// distance rule, and the replay continues until the test fails.  The first pick
+// of a round never needs the test: the global best point (largest value, lowest
+// index among equals) is the best of its own unit, hence published.  Every
+// workgroup replays the same arithmetic on the same records, so all agree on
+// the picks without further communication.
+//
+// The replay comes in two forms (replay_round): by the whole workgroup at once
+// through pairwise bit masks over the live candidates (team_matrix and the
+// settle step; the register-resident kernels), or pick after pick by one wave
+// over candidates put in order once per round (the streaming kernel, where a
+// round is a pass over HBM and the replay is not what binds).
 //
 // "Best" always means largest value, then lowest point index.  Points may be
 // assigned to units in any way; candidates carry their indices, and equal
-// values are detected and resolved on the index wherever they can occur.
+// values are resolved on the index wherever they can occur.
 #pragma once
 #include <type_traits>
 #include "fps_device.h"
@@ -32,7 +39,7 @@ constexpr int kMaxUnits = kMaxGridWG;     // reporting units of a cloud
 constexpr int kRPL = kMaxUnits / kWave;   // unit records per lane of the gathering wave
 constexpr int kSpinLimit = 1 << 19;
 constexpr uint32_t kNoIndex = 0x7fffffffu;  // index of a candidate that does not exist
-constexpr int kSets = 3;                    // the ordered replay takes up to kSets * 64 live candidates
+constexpr int kSets = 3;                    // a replay takes up to kSets * 64 live candidates
 constexpr int kMaxLive = kSets * kWave;
 static_assert(kMaxPicksPerRound <= kMaxLive && kMaxLive <= 256, "a round picks live candidates only");
 

@@ -6,21 +6,20 @@
 // for the whole call.  The strided assignment spreads any run of consecutive
 // indices over all workgroups, so an input that is already in farthest-point
 // order (a layer of a stage chain) yields as many picks per round as any other.
-// A workgroup is one COMMUNICATION wave (wave 0) plus NWK WORKER waves that own
-// the points.  Waves i and i+4 of a workgroup share a SIMD; with NWK + 1 = 4, 8
-// or 16 waves every SIMD carries the same number of waves, one of those of SIMD
-// 0 being the communication wave, whose replay costs about as much arithmetic
-// per pick as a worker wave with one or two points per lane.
+// A workgroup is one COMMUNICATION wave (wave 0) plus NWK = 7 WORKER waves that
+// own the points: eight waves, two per SIMD (waves i and i+4 share one).
 //
 // Workgroups meet once per ROUND (fps_exchange.h), and a round can deliver many
-// picks.  The workers apply the picks of a round to their points one by one,
-// taking them from LDS while the communication wave is still producing them,
-// then reduce their slice to its two best points and an upper bound on every
-// other point (the third-best value).  The communication wave merges the worker
-// waves' results into the workgroup's report, or, when workgroups x worker waves
-// fit the exchange area, passes every wave's result on as a report of its own
-// (more reporting units, more picks per round), and runs the next round.  The
-// picks are exactly those of the one-pick-per-pass loop.
+// picks.  The workers apply the picks of a round to their points, all of which
+// are in LDS by then, reduce their slice to its three best points and an upper
+// bound on every other point (the fourth-best value), help the communication
+// wave with the pairwise work of the replay, and wait for the picks.  The
+// communication wave merges the worker waves' results into the workgroup's
+// report, or, when workgroups x worker waves fit the exchange area, passes
+// every wave's result on as a report of its own (more reporting units, more
+// picks per round), exchanges reports with the other workgroups and settles
+// the picks of the round.  Four workgroup barriers per round.  The picks are
+// exactly those of the one-pick-per-pass loop.
 //
 // Exit: every wait is bounded or ends when the communication wave says so; a
 // workgroup that gives up sets the status word and leaves, and the others then
@@ -31,9 +30,9 @@ namespace ffps {
 
 namespace {
 
-// Candidates a reporting unit contributes to a round.  Three were tried: more
-// picks per round, but a dearer round (larger records, a fourth reduction per
-// merge, half as many candidates again to count and compact) and slower overall.
+// Candidates a reporting unit contributes to a round.  With two a round is
+// cheaper (smaller records, fewer candidates to count and compact) but delivers
+// about 40 % fewer picks.
 constexpr int kT = 3;
 
 struct WaveTop {  // a worker wave's kT best points and the bound on its others
