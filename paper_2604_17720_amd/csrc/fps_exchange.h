@@ -379,26 +379,6 @@ __device__ __forceinline__ void lds_read4x9(uint32_t (&r)[9], const uint32_t (&a
 __device__ __forceinline__ void push_bit(uint32_t &m, uint64_t c) {
     asm("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(m) : "s"(c) : "vcc");
 }
-// The three masks of one candidate: 3 x 24 bytes, one wait.
-__device__ __forceinline__ void lds_read_masks(uint32_t (&k)[6], uint32_t (&l)[6], uint32_t (&b)[6], uint32_t off) {
-    u32x2 r[9];
-    asm volatile("ds_read_b64 %0, %9\n\tds_read_b64 %1, %9 offset:8\n\tds_read_b64 %2, %9 offset:16\n\t"
-                 "ds_read_b64 %3, %9 offset:4608\n\tds_read_b64 %4, %9 offset:4616\n\t"
-                 "ds_read_b64 %5, %9 offset:4624\n\t"
-                 "ds_read_b64 %6, %9 offset:9216\n\tds_read_b64 %7, %9 offset:9224\n\t"
-                 "ds_read_b64 %8, %9 offset:9232\n\t"
-                 "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]),
-                   "=&v"(r[7]), "=&v"(r[8])
-                 : "v"(off) : "memory");
-    static_assert(kMaskPlane == 4608, "offsets of the second and third mask");
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        k[2 * i] = r[i].x; k[2 * i + 1] = r[i].y;
-        l[2 * i] = r[3 + i].x; l[2 * i + 1] = r[3 + i].y;
-        b[2 * i] = r[6 + i].x; b[2 * i + 1] = r[6 + i].y;
-    }
-}
 __device__ __forceinline__ void lds_write2b(uint32_t off, uint32_t v) {
     asm volatile("ds_write_b16 %0, %1" : : "v"(off), "v"(v) : "memory");
 }
@@ -412,8 +392,8 @@ __device__ __forceinline__ void lds_write2b(uint32_t off, uint32_t v) {
 // bits either way round) and let "a before b" mean that a precedes b in the
 // order (value descending, index ascending).  A task takes a slice of 16
 // candidates a and a set of 64 candidates b, one per lane, and writes 16 bits of
-// each of b's masks: d <= T (picking a would put b out of this round); d < value
-// of b (picking a would lower b); a before b.  Bit 31 - (a mod 32) of 32-bit
+// each of b's masks: a before b; that and d <= T (picking a would put b out of
+// this round); that and d < value of b (picking a would lower b).  Bit 31 - (a mod 32) of 32-bit
 // word a / 32 stands for a.  Tasks are dealt out to the waves in turn.  Called by
 // every wave between two workgroup barriers.
 __device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, int W) {
@@ -452,7 +432,9 @@ __device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, in
             mk = __builtin_amdgcn_alignbit(mk, T - d, 31);        // T < d, turned round below
             ml = __builtin_amdgcn_alignbit(ml, d - kb2.y, 31);    // d < value of b
         }
-        mk = ~mk;
+        // the first two masks are only wanted where a comes before b
+        mk = ~mk & mb;
+        ml &= mb;
         // two slices share a 32-bit word, the earlier one in its upper half
         const uint32_t at = mask_off + (uint32_t)b * kMaskRow + (uint32_t)(sl ^ 1) * 2;
         lds_write2b(at, mk);
@@ -824,14 +806,21 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             auto settle = [&](auto ns_tag) {
                 constexpr int NS = decltype(ns_tag)::value;
                 constexpr int NW = 2 * NS;
+                // this lane's masks (plain loads, all in flight together; written by the
+                // other waves before the barrier)
                 uint32_t KB[NS][6], LB[NS][6], BB[NS][6];
 #pragma unroll
-                for (int s = 0; s < NS; ++s)
-                    lds_read_masks(KB[s], LB[s], BB[s], lds_offset(L.mask) + (uint32_t)(lane + s * kWave) * kMaskRow);
-#pragma unroll
                 for (int s = 0; s < NS; ++s) {
+                    const int b = lane + s * kWave;
 #pragma unroll
-                    for (int wd = 0; wd < NW; ++wd) { KB[s][wd] &= BB[s][wd]; LB[s][wd] &= BB[s][wd]; }
+                    for (int wd = 0; wd < NW; wd += 2) {
+                        const u32x2 k2 = *reinterpret_cast<const u32x2 *>(&L.mask[0][b][2 * wd]);
+                        const u32x2 l2 = *reinterpret_cast<const u32x2 *>(&L.mask[1][b][2 * wd]);
+                        const u32x2 b2 = *reinterpret_cast<const u32x2 *>(&L.mask[2][b][2 * wd]);
+                        KB[s][wd] = k2.x; KB[s][wd + 1] = k2.y;
+                        LB[s][wd] = l2.x; LB[s][wd + 1] = l2.y;
+                        BB[s][wd] = b2.x; BB[s][wd + 1] = b2.y;
+                    }
                 }
                 // a set of candidates as mask words (bit 31 - (a mod 32) of word a / 32)
                 auto to_words = [&](const uint64_t (&m)[NS], uint32_t (&wds)[NW]) {
