@@ -374,11 +374,6 @@ __device__ __forceinline__ void lds_read4x9(uint32_t (&r)[9], const uint32_t (&a
                  : "memory");
 }
 
-// One more bit for a mask that is built from its most significant end: m = 2 m + c,
-// where c is a comparison result of this lane (a ballot).
-__device__ __forceinline__ void push_bit(uint32_t &m, uint64_t c) {
-    asm("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(m) : "s"(c) : "vcc");
-}
 __device__ __forceinline__ void lds_write2b(uint32_t off, uint32_t v) {
     asm volatile("ds_write_b16 %0, %1" : : "v"(off), "v"(v) : "memory");
 }
@@ -426,9 +421,11 @@ __device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, in
         for (int e = 0; e < 16; ++e) {
             const uint64_t ka = ((uint64_t)ka2[e].y << 32) | ka2[e].x;
             const uint32_t d = f2u(sqdist(xb, yb, zb, u2f(ra[e].x), u2f(ra[e].y), u2f(ra[e].z)));
-            push_bit(mb, __builtin_amdgcn_ballot_w64(ka > kb));
-            // values are bit patterns of non-negative numbers: the sign of a difference
-            // is the comparison, and it goes into the mask with one funnel shift
+            // a before b: the sign of the 64-bit difference of the keys (both below 2^63)
+            mb = __builtin_amdgcn_alignbit(mb, (uint32_t)((kb - ka) >> 32), 31);
+            // values are bit patterns of non-negative numbers: the sign of a difference is
+            // the comparison, and it goes into the mask (built from its most significant
+            // end: m = 2 m + bit) with one funnel shift
             mk = __builtin_amdgcn_alignbit(mk, T - d, 31);        // T < d, turned round below
             ml = __builtin_amdgcn_alignbit(ml, d - kb2.y, 31);    // d < value of b
         }
