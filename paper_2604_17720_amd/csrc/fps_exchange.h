@@ -676,7 +676,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             count_live();
         }
     }
-    // With at most kMaxLive live candidates the replay needs no argmax per pick.  Put
+    // With at most kMaxLive live candidates the replay needs no argmax per pick.  Take
     // the candidates in the order (value descending, index ascending).  The first
     // one is the next pick.  Picking a point can only lower other values, so the
     // next candidate in that order is the following pick as long as its own value
@@ -686,8 +686,12 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
     // has been lowered to the threshold or below is out of this round and is
     // passed over; one that has been lowered but is still above the threshold
     // may now belong further back in the order, and the round ends before it
-    // (the next round sees it with its new value).  Per pick this costs the
-    // distance update of the candidates and one comparison.
+    // (the next round sees it with its new value).  One wave on its own does this
+    // pick after pick on candidates sorted once per round (the distance update of
+    // the candidates and one comparison per pick); a whole workgroup does it for
+    // all candidates at once from pairwise bit masks (TEAM, further down), where
+    // the round need not end at such a candidate either: its new value is known,
+    // and the round ends only where the order reaches it.
     const bool ordered = total >= 1 && total <= kMaxLive;
     FFPS_SUB(1);
 #ifdef FFPS_PROFILE
@@ -736,8 +740,8 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
 #ifdef FFPS_PROFILE
         oc = clock64();
 #endif
-        // ---- order: every lane ranks its candidates (positions lane, lane + 64, ...)
-        //      by counting the candidates that precede them ----
+        // ---- every lane takes the candidates at positions lane, lane + 64, ... back
+        //      from LDS (sets 0, 1, ...); they are in no particular order yet ----
         const int nsets = (total + kWave - 1) / kWave;  // sets in use
         bool h[kSets];          // this lane has a candidate in set s
         uint32_t a_c[kSets], a_w[kSets], a_i[kSets];  // where to read it (position 0 if it has none)
