@@ -558,6 +558,39 @@ def test_config5_full_size(fb, oracle):
 
 
 @pytest.mark.gpu
+def test_seeded_sweep_of_sizes_batches_and_starts(fb, oracle):
+    """A seeded sweep through the size ranges of the kernels that AUTO selects:
+    random N, B, M and start index, four kinds of cloud (one of them a shuffled
+    integer lattice, i.e. ties everywhere), and the sizes next to the worker-lane
+    multiples of the one-workgroup kernel, with M = N where every point ends up
+    picked.  Indices and squared pick distances, bit for bit."""
+    rng = np.random.default_rng(20260427)
+
+    def shuffled_lattice(n, seed):
+        side = int(round(n ** (1 / 3))) + 1
+        pts = inputs.lattice_grid(side, side, side)[:n]
+        return pts[np.random.default_rng(seed).permutation(n)]
+
+    gens = [inputs.uniform_cube, inputs.shape_cloud, inputs.planes_and_clusters, shuffled_lattice]
+
+    def case(B, N, M, start, variant, gen):
+        x = np.stack([gen(N, int(rng.integers(1 << 30))) for _ in range(B)]).astype(np.float32)
+        _check_exact(fb, oracle, x, M, start, variant)
+
+    for it in range(24):      # one workgroup per cloud
+        N = int(rng.integers(257, 4609))
+        case(int(rng.integers(1, 6)), N, int(rng.integers(1, min(N, 700) + 1)), int(rng.integers(N)), 0, gens[it % 4])
+    for N in (448, 449, 896, 897, 1345, 4481, 4608):
+        case(2, N, min(N, 300), N - 1, WG, gens[N % 4])
+    for N in (449, 897, 1345):
+        case(1, N, N, 0, 0, inputs.uniform_cube)
+    for it in range(16):      # clusters of workgroups
+        N = int(rng.integers(4609, 90000))
+        case(int(rng.integers(1, 5)), N, int(rng.integers(1, 900)), int(rng.integers(N)), 0 if it % 2 else GRID,
+             gens[it % 4])
+
+
+@pytest.mark.gpu
 def test_give_up_path_ends_cleanly_and_the_workspace_stays_usable(fb, oracle):
     """FFPS_ERR_TIMEOUT, forced from the host: with the test knob a workgroup that
     does not find every record at its first look gives up at once; all workgroups
