@@ -19,11 +19,10 @@
 // workgroup replays the same arithmetic on the same records, so all agree on
 // the picks without further communication.
 //
-// The replay comes in two forms (replay_round): by the whole workgroup at once
-// through pairwise bit masks over the live candidates (team_matrix and the
-// settle step; the register-resident kernels), or pick after pick by one wave
-// over candidates put in order once per round (the streaming kernel, where a
-// round is a pass over HBM and the replay is not what binds).
+// The replay (replay_round) is done by the whole workgroup at once, through
+// pairwise bit masks over the live candidates (team_matrix and the settle
+// step); only rounds that can deliver a single pick, or whose candidates do not
+// fit, are replayed pick after pick by one wave.
 //
 // "Best" always means largest value, then lowest point index.  Points may be
 // assigned to units in any way; candidates carry their indices, and equal
@@ -163,53 +162,6 @@ __device__ __forceinline__ u32x4 lds_read16(uint32_t off) {
     return r;
 }
 
-// Two dwords, `d0` and `d1` dwords behind `off` (both below 256), complete on return.
-template <int D0, int D1>
-__device__ __forceinline__ u32x2 lds_read2(uint32_t off) {
-    u32x2 r;
-    asm volatile("ds_read2_b32 %0, %1 offset0:%2 offset1:%3\n\ts_waitcnt lgkmcnt(0)"
-                 : "=v"(r) : "v"(off), "n"(D0), "n"(D1) : "memory");
-    return r;
-}
-// Two 16-byte reads in flight together, complete on return.
-__device__ __forceinline__ void lds_read16x2(u32x4 &a, u32x4 &b, uint32_t off_a, uint32_t off_b) {
-    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&v"(a), "=&v"(b) : "v"(off_a), "v"(off_b) : "memory");
-}
-// Four consecutive 16-byte words (64 bytes from `off`), complete on return.
-__device__ __forceinline__ void lds_read64(u32x4 &a, u32x4 &b, u32x4 &c, u32x4 &d, uint32_t off) {
-    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:16\n\t"
-                 "ds_read_b128 %2, %4 offset:32\n\tds_read_b128 %3, %4 offset:48\n\t"
-                 "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(a), "=&v"(b), "=&v"(c), "=&v"(d) : "v"(off) : "memory");
-}
-// Eight consecutive 16-byte words (128 bytes from `off`), complete on return.
-__device__ __forceinline__ void lds_read128(u32x4 (&r)[8], uint32_t off) {
-    asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:16\n\t"
-                 "ds_read_b128 %2, %8 offset:32\n\tds_read_b128 %3, %8 offset:48\n\t"
-                 "ds_read_b128 %4, %8 offset:64\n\tds_read_b128 %5, %8 offset:80\n\t"
-                 "ds_read_b128 %6, %8 offset:96\n\tds_read_b128 %7, %8 offset:112\n\t"
-                 "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]),
-                   "=&v"(r[6]), "=&v"(r[7])
-                 : "v"(off) : "memory");
-}
-// The records of three candidates, their values (each with the value that
-// follows it in the array) and their indices, with all reads in flight together.
-__device__ __forceinline__ void lds_read_own(u32x4 (&c)[3], u32x2 (&w)[3], uint32_t (&i)[3],
-                                             const uint32_t (&a_c)[3], const uint32_t (&a_w)[3],
-                                             const uint32_t (&a_i)[3]) {
-    asm volatile("ds_read_b128 %0, %9\n\tds_read_b128 %1, %10\n\tds_read_b128 %2, %11\n\t"
-                 "ds_read2_b32 %3, %12 offset1:1\n\tds_read2_b32 %4, %13 offset1:1\n\t"
-                 "ds_read2_b32 %5, %14 offset1:1\n\t"
-                 "ds_read_b32 %6, %15\n\tds_read_b32 %7, %16\n\tds_read_b32 %8, %17\n\t"
-                 "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(c[0]), "=&v"(c[1]), "=&v"(c[2]), "=&v"(w[0]), "=&v"(w[1]), "=&v"(w[2]),
-                   "=&v"(i[0]), "=&v"(i[1]), "=&v"(i[2])
-                 : "v"(a_c[0]), "v"(a_c[1]), "v"(a_c[2]), "v"(a_w[0]), "v"(a_w[1]), "v"(a_w[2]),
-                   "v"(a_i[0]), "v"(a_i[1]), "v"(a_i[2])
-                 : "memory");
-}
 // The records of three candidates and their 8-byte keys, all reads in flight together.
 __device__ __forceinline__ void lds_read_own_keys(u32x4 (&c)[3], u32x2 (&k)[3], const uint32_t (&a_c)[3],
                                                   const uint32_t (&a_k)[3]) {
@@ -222,11 +174,6 @@ __device__ __forceinline__ void lds_read_own_keys(u32x4 (&c)[3], u32x2 (&k)[3], 
 }
 __device__ __forceinline__ void lds_write4(uint32_t off, uint32_t v) {
     asm volatile("ds_write_b32 %0, %1" : : "v"(off), "v"(v) : "memory");
-}
-__device__ __forceinline__ uint32_t lds_read4(uint32_t off) {
-    uint32_t r;
-    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(off) : "memory");
-    return r;
 }
 // 8-byte LDS word written and read by one instruction each.
 __device__ __forceinline__ void lds_write8(uint32_t off, u32x2 v) {
@@ -311,19 +258,17 @@ struct RoundLds {
     // picks of the round: {x, y, z, seq}; spare slots that are never picks (they
     // keep the seed point), so that readers may read a few slots past the last pick
     __attribute__((aligned(16))) u32x4 pk[kMaxPicksPerRound + 8];
-    uint32_t pk_idx[kMaxPicksPerRound];  // index of each pick of the round (general replay loop)
+    uint32_t pk_idx[kMaxPicksPerRound];  // index of each pick of the round (pick-after-pick loop)
     uint32_t pk_val[kMaxPicksPerRound];  // and the value it was picked with
-    // live candidates, first in compaction order, then in the order of the replay;
-    // behind each array 64 entries, one per lane, take what the compaction discards
-    // (one common entry would make every such write a 64-way bank conflict)
-    __attribute__((aligned(16))) u32x4 cand[kMaxLive + 4 + kWave];  // {x, y, z, value; later sequence number}
-    __attribute__((aligned(16))) uint32_t keyw[kMaxLive + 32 + kWave];  // 32-bit sort keys, zero-padded; later the values in order
-    __attribute__((aligned(16))) uint32_t idxw[kMaxLive + 4 + kWave];   // point indices
+    // live candidates in compaction order; behind each array 64 entries, one per
+    // lane, take what the compaction discards (one common entry would make every
+    // such write a 64-way bank conflict)
+    __attribute__((aligned(16))) u32x4 cand[kMaxLive + 4 + kWave];   // {x, y, z, value}
+    __attribute__((aligned(16))) u32x2 key64[kMaxLive + 4 + kWave];  // {complement of the index, value}: compares as the order does
     // replay by the whole workgroup: number of live candidates (0: nothing to do this
     // round) and the threshold, then for every candidate b three bit masks over the
     // candidates a, in slices of 16: a lowers b to the threshold or below / a lowers b
     // / a comes before b in the order; the first two only where a comes before b
-    __attribute__((aligned(16))) u32x2 key64[kMaxLive + 4 + kWave];  // {complement of the index, value}: compares as the order does
     __attribute__((aligned(8))) uint32_t team_total, team_T;
     __attribute__((aligned(8))) uint16_t mask[3][kMaxLive][kMaxLive / 16];
 };
@@ -333,11 +278,11 @@ static_assert(kMaskRow == 24, "a mask row is read as three 8-byte words");
 
 // Counters of a profiling build (workgroup 0 only).
 struct RoundProf {
-    uint32_t acc[8];   // 100 MHz ticks per phase; [5], [6]: rounds of the ordered replay with up to 64 / more candidates; [7]: polls
-    uint32_t loop[4];  // shader cycles and picks inside the ordered replay's pick loop, by the same split
-    uint32_t sub[4];   // shader cycles of the replay set-up: bounds, counting, compaction, ordering
-    uint32_t ev[4];    // live candidates, candidates passed over, rounds ended by a lowered candidate, exact re-orderings
-    uint32_t ord[6];   // shader cycles inside the ordering: own load, first barrier, ranking share, second barrier, placing, rest
+    uint32_t acc[8];   // 100 MHz ticks per phase; [5], [6]: rounds replayed by the workgroup with up to 64 / more live candidates; [7]: polls
+    uint32_t loop[4];  // [1], [3]: picks of those rounds, by the same split
+    uint32_t sub[4];   // shader cycles inside the replay: bounds, counting, compaction, work of the whole workgroup
+    uint32_t ev[4];    // [0]: live candidates; [2]: rounds ended by a lowered candidate
+    uint32_t ord[6];   // shader cycles of that work: own candidates back from LDS, first barrier, share of the masks, second barrier, settling
     uint64_t last;
 };
 #ifdef FFPS_PROFILE
@@ -360,18 +305,6 @@ struct RoundProf {
 __device__ __forceinline__ void team_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
     __syncthreads();
-}
-
-// Nine words from nine addresses per lane, one wait.
-__device__ __forceinline__ void lds_read4x9(uint32_t (&r)[9], const uint32_t (&a)[9]) {
-    asm volatile("ds_read_b32 %0, %9\n\tds_read_b32 %1, %10\n\tds_read_b32 %2, %11\n\t"
-                 "ds_read_b32 %3, %12\n\tds_read_b32 %4, %13\n\tds_read_b32 %5, %14\n\t"
-                 "ds_read_b32 %6, %15\n\tds_read_b32 %7, %16\n\tds_read_b32 %8, %17\n\t"
-                 "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]),
-                   "=&v"(r[7]), "=&v"(r[8])
-                 : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(a[8])
-                 : "memory");
 }
 
 __device__ __forceinline__ void lds_write2b(uint32_t off, uint32_t v) {
@@ -441,107 +374,19 @@ __device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, in
     }
 }
 
-// The inner loop of the ordered replay, for one set of candidates (lane L holds
-// candidate L of the set: current value v, coordinates x, y, z; `o` is the value
-// it had at the start of the round, or 0xffffffff for the lanes from `lim` on,
-// where the set ends; `seq` is the sequence number the candidate has as a pick
-// and `a_pk` the address of the LDS slot it goes to, both per lane).  Starting
-// at candidate i, with `bit` = 1 << i:
-//   - candidate i's value is unchanged (v == o in lane i): lane i alone writes
-//     its record {x, y, z, seq} to its slot for the worker waves, its
-//     coordinates are read out of the lane, every lane's value is lowered by
-//     the squared distance to it, and i steps on (21 instructions, nothing to
-//     wait for: LDS is only written).  The distances are worked out before the
-//     branch on the comparison, whose way from the vector to the scalar unit is
-//     long; a candidate that turns out lowered has cost eight wasted operations;
-//   - it has been lowered to the threshold T or below: it is out of this round;
-//     its bit is noted in `gone`, the sequence numbers and slots of all lanes
-//     move down by one, and i steps on.  With `soft` set the block returns here
-//     instead (the caller then moves the end of the set, which depends on the
-//     number of candidates passed over when the picks left to do are few);
-//   - it has been lowered but is still above T, or i has reached `lim`: return.
-// The registers named in the text are scratch of this block; distances are the
-// individually rounded operations of sqdist; a lane read into a scalar register
-// needs two instructions before a vector instruction may use it, which the
-// order of the reads provides.
-__device__ __forceinline__ void ordered_run(uint32_t &v, uint32_t o, float x, float y, float z,
-                                            uint32_t seq, uint32_t a_pk, uint64_t &bit, int &i,
-                                            uint64_t &gone, uint32_t T, int lim, int soft) {
-    uint32_t sx, sy, sz;
-#define FFPS_STEP                                          \
-    "v_readlane_b32 %[sx], %[x], %[i]\n\t"                 \
-    "v_readlane_b32 %[sy], %[y], %[i]\n\t"                 \
-    "v_readlane_b32 %[sz], %[z], %[i]\n\t"                 \
-    "v_cmp_eq_u32 vcc, %[v], %[o]\n\t"                     \
-    "v_subrev_f32 v112, %[sx], %[x]\n\t"                   \
-    "v_subrev_f32 v113, %[sy], %[y]\n\t"                   \
-    "v_subrev_f32 v114, %[sz], %[z]\n\t"                   \
-    "v_mul_f32 v112, v112, v112\n\t"                       \
-    "v_mul_f32 v113, v113, v113\n\t"                       \
-    "v_mul_f32 v114, v114, v114\n\t"                       \
-    "v_add_f32 v112, v112, v113\n\t"                       \
-    "v_add_f32 v112, v112, v114\n\t"                       \
-    "s_and_b64 vcc, vcc, %[bit]\n\t"                       \
-    "s_cbranch_scc0 7f\n\t"                                \
-    "s_mov_b64 exec, vcc\n\t"                              \
-    "ds_write_b128 %[ap], v[108:111]\n\t"                  \
-    "s_mov_b64 exec, -1\n\t"                               \
-    "v_min_f32 %[v], %[v], v112\n\t"                       \
-    "s_lshl_b64 %[bit], %[bit], 1\n\t"                     \
-    "s_add_i32 %[i], %[i], 1\n\t"
-    // The compiler does not hold back a block that overwrites a register named
-    // in its clobber list while a load into that register is still in flight (it
-    // reloads values it keeps in v108 .. v114 after the block, and the block may
-    // be entered again before such a reload has landed): the block waits for all
-    // outstanding loads itself before it touches those registers.
-    asm volatile(
-        "s_waitcnt vmcnt(0) lgkmcnt(0)\n\t"
-        "v_mov_b32 v108, %[x]\n\t"
-        "v_mov_b32 v109, %[y]\n\t"
-        "v_mov_b32 v110, %[z]\n\t"
-        "v_mov_b32 v111, %[seq]\n\t"
-        "1:\n\t"
-        FFPS_STEP
-        FFPS_STEP
-        "s_branch 1b\n\t"
-        "7:\n\t"
-        "s_cmp_ge_i32 %[i], %[lim]\n\t"
-        "s_cbranch_scc1 9f\n\t"
-        "s_cmp_lg_u32 %[soft], 0\n\t"
-        "s_cbranch_scc1 9f\n\t"
-        "v_readlane_b32 %[sx], %[v], %[i]\n\t"
-        "s_nop 1\n\t"
-        "s_cmp_gt_u32 %[sx], %[T]\n\t"
-        "s_cbranch_scc1 9f\n\t"
-        "s_or_b64 %[gone], %[gone], %[bit]\n\t"
-        "v_subrev_u32 v111, 1, v111\n\t"
-        "v_subrev_u32 %[ap], 16, %[ap]\n\t"
-        "s_lshl_b64 %[bit], %[bit], 1\n\t"
-        "s_add_i32 %[i], %[i], 1\n\t"
-        "s_branch 1b\n\t"
-        "9:\n\t"
-        : [v] "+v"(v), [bit] "+s"(bit), [i] "+s"(i), [gone] "+s"(gone), [ap] "+v"(a_pk), [sx] "=&s"(sx),
-          [sy] "=&s"(sy), [sz] "=&s"(sz)
-        : [o] "v"(o), [x] "v"(x), [y] "v"(y), [z] "v"(z), [seq] "v"(seq), [T] "s"(T), [lim] "s"(lim),
-          [soft] "s"(soft)
-        : "memory", "vcc", "scc", "v108", "v109", "v110", "v111", "v112", "v113", "v114");
-#undef FFPS_STEP
-}
-
 // Replay of the greedy rule of Eq. 1 on KC candidates per lane of ONE full wave
 // (value bits cv, point index ci, coordinates cx/cy/cz; a candidate that does
 // not exist has value 0 and index kNoIndex), given lb = the lane's share of the
 // bounds on all points that are not candidates.  Pick number c of the round is
-// written as {x, y, z, npicked + c} to L.pk[c] (16-byte LDS writes, in pick
-// order, so other waves may consume them while the replay is still running),
-// and what record_picks needs to name its index and value is left in L.
+// written as {x, y, z, npicked + c} to L.pk[c] (16-byte LDS writes), and what
+// record_picks needs to name its index and value is left in the lanes or in L.
 // Returns the number of picks (1 .. cap) and how they were noted.  The
 // candidate arrays are used up.
 struct RoundResult {
     int cnt;        // picks of the round, or -1 when the round failed
     bool by_lane;   // picks noted in the lanes (below) rather than in L.pk_idx / L.pk_val
-    // by_lane: what this lane's candidates of the ordered replay became: pick
-    // number within the round (-1: not picked), point index, value when picked
+    // by_lane: what this lane's live candidates became: pick number within the
+    // round (-1: not picked), point index, value when picked
     int pc[kSets];
     uint32_t pi[kSets], pv[kSets];
 };
@@ -551,20 +396,21 @@ struct RoundResult {
 __device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const RoundResult &r,
                                              int npicked, int32_t *idx_out, float *md_out);
 
-// With TEAM the other waves of the workgroup take part in the replay: they
+// The other team_waves - 1 waves of the workgroup take part in the replay: they
 // wait at a workgroup barrier after handing in their reports, call team_matrix
 // and pass a second barrier, every round; this function passes the same two
-// barriers exactly once, whatever path the round takes.  live_sets (1 .. kSets)
+// barriers exactly once, whatever path the round takes.  MAXS (1 .. kSets) is the
+// largest number of sets of 64 live candidates the caller wants code for.  live_sets (1 .. kSets)
 // limits the live candidates to that many per lane: the pairwise work grows with
 // the square of their number, and where a round ends after a few tens of picks
 // anyway (small clouds) the candidates further down the order are not reached.
 // live_target > 0 asks for about that many live candidates in all, for the same
 // reason.
-template <int KC, bool TEAM = false>
+template <int KC, int MAXS = kSets>
 __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint32_t (&cv)[KC],
                                             uint32_t (&ci)[KC], float (&cx)[KC], float (&cy)[KC],
                                             float (&cz)[KC], uint32_t lb, int npicked, int cap,
-                                            RoundProf *prof, int team_waves = 1, int live_sets = kSets,
+                                            RoundProf *prof, int team_waves, int live_sets = MAXS,
                                             int live_target = 0) {
     const uint32_t pk_off = lds_offset(L.pk);
 #ifdef FFPS_PROFILE
@@ -666,6 +512,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 t[0] = umax(t[0], v);
             }
             T = umax(Bound, wave_max_u32(live_sets == 1 ? t[1] : live_sets == 2 ? t[2] : t[kSets]));
+            static_assert(MAXS >= 1 && MAXS <= kSets, "sets of 64 live candidates");
             count_live();
         }
         if (live_target > 0 && total > live_target + live_target / 4) {
@@ -676,23 +523,20 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             count_live();
         }
     }
-    // With at most kMaxLive live candidates the replay needs no argmax per pick.  Take
+    // With at most MAXS * 64 live candidates the replay needs no argmax per pick.  Take
     // the candidates in the order (value descending, index ascending).  The first
     // one is the next pick.  Picking a point can only lower other values, so the
     // next candidate in that order is the following pick as long as its own value
     // has not been lowered by a pick of this round: everything behind it started
-    // no higher and has not grown, candidates ahead of it are picked or gone, and
-    // unreported points are at or below the threshold.  A candidate whose value
-    // has been lowered to the threshold or below is out of this round and is
-    // passed over; one that has been lowered but is still above the threshold
-    // may now belong further back in the order, and the round ends before it
-    // (the next round sees it with its new value).  One wave on its own does this
-    // pick after pick on candidates sorted once per round (the distance update of
-    // the candidates and one comparison per pick); a whole workgroup does it for
-    // all candidates at once from pairwise bit masks (TEAM, further down), where
-    // the round need not end at such a candidate either: its new value is known,
-    // and the round ends only where the order reaches it.
-    const bool ordered = total >= 1 && total <= kMaxLive;
+    // no higher and has not grown, candidates ahead of it are picked or out of
+    // the round, and unreported points are at or below the threshold.  A candidate
+    // whose value has been lowered to the threshold or below is out of this
+    // round and is passed over; one that has been lowered but is still above the
+    // threshold belongs further back in the order, at its new value, and the
+    // round ends where the order reaches that value (the next round sees the
+    // candidate again).  All of this is decided for all candidates at once from
+    // pairwise bit masks (further down).
+    const bool ordered = total >= 1 && total <= MAXS * kWave;
     FFPS_SUB(1);
 #ifdef FFPS_PROFILE
     if (prof && ordered) prof->acc[total <= kWave ? 5 : 6] += 1;
@@ -705,36 +549,24 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
         res.pv[s] = 0u;
     }
     if (ordered) {
-        const uint32_t cand_off = lds_offset(L.cand), key_off = lds_offset(L.keyw),
-                       idx_off = lds_offset(L.idxw);
-        // 32-bit sort key of a live candidate: its value above the threshold and its
-        // compaction position, (value - T) << 8 | position, which orders by value
-        // and is unique.  Candidates of equal value come out in position order
-        // rather than index order; that is detected below and then put right.
-        const bool narrow = V - T < (1u << 24);
+        const uint32_t cand_off = lds_offset(L.cand), key64_off = lds_offset(L.key64);
         // compaction without branches: a candidate that is not live goes to the
         // lane's own slot behind the live ones, which nobody reads
         {
-            const uint32_t dump_c = (uint32_t)(kMaxLive + 4 + lane), dump_k = (uint32_t)(kMaxLive + 32 + lane);
+            const uint32_t dump = (uint32_t)(kMaxLive + 4 + lane);
             uint32_t pos = (uint32_t)before;
 #pragma unroll
             for (int q = 0; q < KC; ++q) {
                 const bool live = cv[q] > T;
                 u32x4 r;
                 r.x = f2u(cx[q]); r.y = f2u(cy[q]); r.z = f2u(cz[q]); r.w = cv[q];
-                lds_write16(cand_off + (live ? pos : dump_c) * 16, r);
-                if constexpr (TEAM) {
-                    u32x2 k2;
-                    k2.x = ~ci[q]; k2.y = cv[q];
-                    lds_write8(lds_offset(L.key64) + (live ? pos : dump_c) * 8, k2);
-                } else {
-                    lds_write4(key_off + (live ? pos : dump_k) * 4, ((cv[q] - T) << 8) | pos);
-                    lds_write4(idx_off + (live ? pos : dump_c) * 4, ci[q]);
-                }
+                lds_write16(cand_off + (live ? pos : dump) * 16, r);
+                u32x2 k2;
+                k2.x = ~ci[q]; k2.y = cv[q];
+                lds_write8(key64_off + (live ? pos : dump) * 8, k2);
                 pos += live ? 1u : 0u;
             }
         }
-        if (!TEAM && lane < 32) lds_write4(key_off + (total + lane) * 4, 0u);  // padding: below every key
         // the same wave wrote and now reads: LDS keeps its accesses in order
         FFPS_SUB(2);
 #ifdef FFPS_PROFILE
@@ -744,32 +576,24 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
         //      from LDS (sets 0, 1, ...); they are in no particular order yet ----
         const int nsets = (total + kWave - 1) / kWave;  // sets in use
         bool h[kSets];          // this lane has a candidate in set s
-        uint32_t a_c[kSets], a_w[kSets], a_i[kSets];  // where to read it (position 0 if it has none)
+        uint32_t a_c[kSets], a_k[kSets];  // where to read it (position 0 if it has none)
 #pragma unroll
         for (int s = 0; s < kSets; ++s) {
             const int p = lane + s * kWave;
             h[s] = p < total;
             const uint32_t q = h[s] ? (uint32_t)p : 0u;
-            a_c[s] = cand_off + q * 16; a_w[s] = key_off + q * 4; a_i[s] = idx_off + q * 4;
+            a_c[s] = cand_off + q * 16; a_k[s] = key64_off + q * 8;
         }
         u32x4 c[kSets];
-        u32x2 w[kSets];
+        u32x2 k2[kSets];
         uint32_t ix[kSets], o[kSets];  // index; value at the start of the round
-        if constexpr (TEAM) {
-            u32x2 k2[kSets];
-            uint32_t a_k[kSets];
+        lds_read_own_keys(c, k2, a_c, a_k);
 #pragma unroll
-            for (int s = 0; s < kSets; ++s) a_k[s] = lds_offset(L.key64) + (h[s] ? (uint32_t)(lane + s * kWave) : 0u) * 8;
-            lds_read_own_keys(c, k2, a_c, a_k);
-#pragma unroll
-            for (int s = 0; s < kSets; ++s) ix[s] = ~k2[s].x;
-        } else {
-            lds_read_own(c, w, ix, a_c, a_w, a_i);
-        }
+        for (int s = 0; s < kSets; ++s) ix[s] = ~k2[s].x;
 #pragma unroll
         for (int s = 0; s < kSets; ++s) o[s] = h[s] ? c[s].w : 0u;
         FFPS_ORD(0);
-        if constexpr (TEAM) {
+        {
             // ---- replay by the whole workgroup: no order, no pick after pick.  The
             //      other waves work out, for every pair of live candidates, which one
             //      comes first and what picking it does to the other (team_matrix).
@@ -788,7 +612,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 lds_write16(cand_off + (uint32_t)(total + lane) * 16, zr);
                 u32x2 z2;
                 z2.x = 0u; z2.y = 0u;
-                lds_write8(lds_offset(L.key64) + (uint32_t)(total + lane) * 8, z2);
+                lds_write8(key64_off + (uint32_t)(total + lane) * 8, z2);
             }
             if (lane == 0) {
                 u32x2 hd;
@@ -929,9 +753,9 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 }
             };
             static_assert(kSets == 3, "one case per number of sets");
-            if (nsets == 1) settle(std::integral_constant<int, 1>{});
-            else if (nsets == 2) settle(std::integral_constant<int, 2>{});
-            else settle(std::integral_constant<int, 3>{});
+            if (nsets == 1 || MAXS == 1) settle(std::integral_constant<int, 1>{});
+            else if (nsets == 2 || MAXS == 2) settle(std::integral_constant<int, 2>{});
+            else if constexpr (MAXS >= 3) settle(std::integral_constant<int, 3>{});
             FFPS_ORD(4);
             FFPS_SUB(3);
 #ifdef FFPS_PROFILE
@@ -941,239 +765,15 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 prof->loop[total <= kWave ? 1 : 3] += cnt;
             }
 #endif
-        } else {
-        bool ties = false;
-        // Candidates go to their places in the order: records {x, y, z, sequence
-        // number as a pick if no candidate ahead is passed over}, values and indices.
-        // Every lane then takes candidates number lane, lane + 64, ... of the order
-        // (sets 0, 1, ...) and sees whether the candidate behind each of them has
-        // the same value.
-        auto place = [&](const int (&r)[kSets]) {
-#pragma unroll
-            for (int s = 0; s < kSets; ++s) {
-                if (h[s]) {
-                    c[s].w = (uint32_t)(npicked + r[s]);
-                    lds_write16(cand_off + r[s] * 16, c[s]);
-                    lds_write4(key_off + r[s] * 4, o[s]);
-                    lds_write4(idx_off + r[s] * 4, ix[s]);
-                }
-            }
-            if (lane == 0) lds_write4(key_off + total * 4, 0u);  // behind the last value
-            lds_read_own(c, w, ix, a_c, a_w, a_i);
-            bool tie = false;
-#pragma unroll
-            for (int s = 0; s < kSets; ++s) {
-                o[s] = h[s] ? w[s].x : 0u;
-                tie = tie || (h[s] && w[s].y == w[s].x);
-            }
-            ties = __builtin_amdgcn_ballot_w64(tie) != 0;
-        };
-        // by (value descending, index ascending) on the full values: always right
-        auto order_exact = [&]() {
-            uint64_t key[kSets];
-            int r[kSets];
-#pragma unroll
-            for (int s = 0; s < kSets; ++s) {
-                key[s] = ((uint64_t)o[s] << 32) | ~ix[s];
-                r[s] = 0;
-            }
-            for (int j = 0; j < total; ++j) {
-                const uint64_t kj = ((uint64_t)lds_read4(key_off + j * 4) << 32) | ~lds_read4(idx_off + j * 4);
-#pragma unroll
-                for (int s = 0; s < kSets; ++s) r[s] += kj > key[s] ? 1 : 0;
-            }
-            place(r);
-        };
-        if (narrow) {
-            int r[kSets];
-            {
-                uint32_t key[kSets];
-#pragma unroll
-                for (int s = 0; s < kSets; ++s) {
-                    key[s] = ((o[s] - T) << 8) | (uint32_t)(lane + s * kWave);
-                    r[s] = 0;
-                }
-                for (int j = 0; j < total; j += 32) {
-                    // thirty-two keys per step, read by all lanes from the same addresses (a broadcast)
-                    u32x4 k[8];
-                    lds_read128(k, key_off + j * 4);
-#pragma unroll
-                    for (int s = 0; s < kSets; ++s) {
-                        if (s < nsets) {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) {
-                                r[s] += k[e].x > key[s] ? 1 : 0; r[s] += k[e].y > key[s] ? 1 : 0;
-                                r[s] += k[e].z > key[s] ? 1 : 0; r[s] += k[e].w > key[s] ? 1 : 0;
-                            }
-                        }
-                    }
-                }
-            }
-            place(r);
-            FFPS_ORD(4);
-            // The values are in LDS in order now: equal neighbours are candidates of
-            // equal value, which the 32-bit keys put in position order where index
-            // order is wanted.  The values of a round lie in a narrow band, so among a
-            // hundred of them two that agree in every bit are common.  Two such
-            // neighbours change places when their indices say so; three or more in a
-            // row (rare) are left to the exact ordering.
-            if (ties) {
-                bool lng = false, mv = false;
-                int np[kSets];
-                // value and index of the candidate before each of this lane's, index of
-                // the one behind it (position 0 where there is none)
-                uint32_t nb[3 * kSets], na[3 * kSets];
-#pragma unroll
-                for (int s = 0; s < kSets; ++s) {
-                    const int p = lane + s * kWave;
-                    const uint32_t pb = h[s] && p > 0 ? (uint32_t)(p - 1) : 0u;
-                    const uint32_t pa = p + 1 < total ? (uint32_t)(p + 1) : 0u;
-                    na[3 * s] = key_off + pb * 4; na[3 * s + 1] = idx_off + pb * 4; na[3 * s + 2] = idx_off + pa * 4;
-                }
-                lds_read4x9(nb, na);
-#pragma unroll
-                for (int s = 0; s < kSets; ++s) {
-                    const int p = lane + s * kWave;
-                    np[s] = p;
-                    if (h[s]) {
-                        const uint32_t vb = nb[3 * s], ib = nb[3 * s + 1], ia = nb[3 * s + 2];
-                        const uint32_t va = w[s].y;  // keyw[p + 1]; zero behind the last one
-                        const bool eb = p > 0 && vb == o[s], ea = va == o[s];
-                        lng = lng || (eb && ea);
-                        if (ea && ia < ix[s]) np[s] = p + 1;       // the one behind has the lower index
-                        else if (eb && ib > ix[s]) np[s] = p - 1;  // the one before has the higher index
-                        mv = mv || np[s] != p;
-                    }
-                }
-#ifdef FFPS_PROFILE
-                if (prof && __builtin_amdgcn_ballot_w64(lng) != 0) prof->ev[3] += 1;
-#endif
-                if (__builtin_amdgcn_ballot_w64(lng) != 0) {
-                    order_exact();
-                } else if (__builtin_amdgcn_ballot_w64(mv) != 0) {
-                    place(np);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int s = 0; s < kSets; ++s)
-                if (h[s] || s == 0) lds_write4(a_w[s], c[s].w);  // order_exact reads the values there
-            order_exact();
         }
-        float x[kSets], y[kSets], z[kSets];
-        uint32_t v[kSets];  // current values
-#pragma unroll
-        for (int s = 0; s < kSets; ++s) {
-            x[s] = u2f(c[s].x); y[s] = u2f(c[s].y); z[s] = u2f(c[s].z);
-            v[s] = o[s];
-        }
-        FFPS_ORD(5);
-        FFPS_SUB(3);
-#ifdef FFPS_PROFILE
-        const uint64_t lc0 = clock64();
-#endif
-        // ---- replay, one set after the other ----
-        uint64_t gone[kSets] = {};  // candidates passed over
-        int ngone = 0;
-        bool stop = false;
-        // Candidates [base, base + n) of the order are lanes 0 .. n-1 of a set.
-        // Candidate base + li is pick number base + li - ngone of the round, so with
-        // `cap` picks allowed the set ends at lane cap + ngone - base.  Returns the
-        // number of candidates of the set that were dealt with.
-        auto run_set = [&](uint32_t &vs, uint32_t os, float xs, float ys, float zs, int base, int n,
-                           uint64_t &gs) {
-            int li = 0;
-            while (true) {
-                // the end of the set moves with the candidates passed over only when
-                // fewer picks are left to do than the set has candidates
-                const bool soft = cap - base < n;
-                const int lend = soft ? (n < cap + ngone - base ? n : cap + ngone - base) : n;
-                if (li >= lend) break;
-                const int pc = base + lane - ngone;  // this lane's candidate as a pick of the round
-                uint64_t bit = 1ull << li;
-                const uint64_t gone_before = gs;
-                ordered_run(vs, lane < lend ? os : 0xffffffffu, xs, ys, zs, (uint32_t)(npicked + pc),
-                            pk_off + (uint32_t)pc * 16, bit, li, gs,
-                            (uint32_t)__builtin_amdgcn_readfirstlane((int)T),
-                            __builtin_amdgcn_readfirstlane(lend),
-                            __builtin_amdgcn_readfirstlane(soft ? 1 : 0));
-                ngone += __builtin_popcountll(gs ^ gone_before);
-                if (li >= lend) break;
-                // candidate li has been lowered by a pick of this round
-                if ((uint32_t)readlane_i((int)vs, li) > T) {
-                    stop = true;  // still a candidate, but maybe no longer the next one
-                    break;
-                }
-                // out of this round: the candidates behind it become picks one number earlier
-                gs |= 1ull << li;
-                ++ngone;
-                ++li;
-            }
-            return li;
-        };
-        int dealt[kSets] = {};  // candidates of each set that were dealt with
-#pragma unroll
-        for (int s = 0; s < kSets; ++s) {
-            const int base = s * kWave;
-            if (stop || base >= total || cap + ngone <= base) break;
-            if (s > 0) {
-                if (dealt[s - 1] < kWave) break;
-                // This set has not seen the picks of the sets before it: apply them (the
-                // workers are busy with the same picks meanwhile), eight slots per LDS
-                // read.  Slots behind the picks of this round hold picks of earlier
-                // rounds (or the seed point), which every value already reflects, so
-                // applying those again changes nothing.
-                const int done = base - ngone;
-                for (int k0 = 0; k0 < done; k0 += 8) {
-                    u32x4 rr[8];
-                    lds_read128(rr, pk_off + k0 * 16);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        v[s] = f2u(min_dist(u2f(v[s]), sqdist(x[s], y[s], z[s], u2f(rr[e].x), u2f(rr[e].y),
-                                                              u2f(rr[e].z))));
-                }
-            }
-            const int n = total - base < kWave ? total - base : kWave;
-            dealt[s] = run_set(v[s], o[s], x[s], y[s], z[s], base, n, gone[s]);
-            cnt += dealt[s];
-        }
-        cnt -= ngone;
-#ifdef FFPS_PROFILE
-        if (prof) {
-            prof->ev[0] += (uint32_t)total;
-            prof->ev[1] += (uint32_t)ngone;
-            prof->ev[2] += stop ? 1u : 0u;
-        }
-#endif
-        // the candidates dealt with were picked unless passed over; the pick number
-        // of one of them is its place minus the candidates passed over before it
-        int gone_before_set = 0;
-#pragma unroll
-        for (int s = 0; s < kSets; ++s) {
-            const int g = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(gone[s] >> 32),
-                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)gone[s], 0u));
-            if (lane < dealt[s] && !((gone[s] >> lane) & 1ull))
-                res.pc[s] = lane + s * kWave - gone_before_set - g;
-            gone_before_set += __builtin_popcountll(gone[s]);
-            res.pi[s] = ix[s];
-            res.pv[s] = o[s];
-        }
-#ifdef FFPS_PROFILE
-        if (prof) {
-            prof->loop[total <= kWave ? 0 : 2] += (uint32_t)(clock64() - lc0);
-            prof->loop[total <= kWave ? 1 : 3] += cnt;
-        }
-#endif
-        }  // the wave's own ordered replay
     } else {
         // a single pick (best candidate not above the bound, or cap 1), or more
-        // than kMaxLive candidates above every threshold tried: work on all
-        // candidates of every lane
-        if (TEAM) {
-            if (lane == 0) lds_write4(lds_offset(&L.team_total), 0u);
-            team_barrier();
-            team_barrier();
-        }
+        // live candidates than fit above every threshold tried: this wave works
+        // pick after pick on all candidates of every lane.  The other waves wait at
+        // the two barriers of the replay: nothing for them to do.
+        if (lane == 0) lds_write4(lds_offset(&L.team_total), 0u);
+        team_barrier();
+        team_barrier();
         while (true) {
             uint32_t bv, bi;
             int bq;
@@ -1216,16 +816,16 @@ __device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const 
 // One round, run by ONE full wave of a workgroup.  The cloud has U reporting
 // units (a whole workgroup, or each of its worker waves); lanes 0 .. nsub-1 of
 // this wave publish `in` as unit unit0 + lane.  The wave then gathers all U
-// records, replays, writes each pick as {x, y, z, npicked + c} to L.pk[c]
-// (16-byte LDS writes, in pick order, so other waves may consume them while
-// the replay is still running).  Returns the picks of the round (1 .. cap; see
-// record_picks), or a count of -1 after setting *status when another unit's
-// record never arrived.
-template <int T, bool TEAM = false>
+// records and replays with the help of the workgroup's other team_waves - 1 waves
+// (replay_round), which leaves each pick as {x, y, z, npicked + c} in L.pk[c].
+// Returns the picks of the round (1 .. cap; see record_picks), or a count of -1
+// after setting *status when another unit's record never arrived (the two
+// barriers of the replay have not been passed then).
+template <int T, int MAXS = kSets>
 __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchange, int U, int unit0,
                                                       int nsub, int lane, uint32_t round,
                                                       const RoundInput<T> &in, int npicked, int cap,
-                                                      int *status, RoundProf *prof, int team_waves = 1,
+                                                      int *status, RoundProf *prof, int team_waves,
                                                       int live_target = 0, int spin_limit = kSpinLimit) {
     static_assert(T == 2 || T == 3, "two or three candidates per unit");
     constexpr int NCH = chunks_of(T);
@@ -1318,8 +918,8 @@ __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchang
         const uint32_t bnd = T == 2 ? r[0][q].z : r[NCH - 1][q].x;
         lb = umax(lb, present ? bnd : 0u);
     }
-    return replay_round<KC, TEAM>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof, team_waves, kSets,
-                                  live_target);
+    return replay_round<KC, MAXS>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof, team_waves, MAXS,
+                                        live_target);
 }
 
 }  // namespace ffps

@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             }
             in.bound = o.t.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
-            res = exchange_round<kT, true>(L, a.exchange, G * NWK, w * NWK, NWK, lane, round, in, npicked,
+            res = exchange_round<kT>(L, a.exchange, G * NWK, w * NWK, NWK, lane, round, in, npicked,
                                            cap, a.status, prof, NWK + 1, 0, a.spin_limit);
         } else {
             // ---- 2a. the workgroup's kT best + bound from the worker waves' ----
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             }
             in.bound = g3.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
-            res = exchange_round<kT, true>(L, a.exchange, G, w, 1, lane, round, in, npicked, cap,
+            res = exchange_round<kT>(L, a.exchange, G, w, 1, lane, round, in, npicked, cap,
                                            a.status, prof, NWK + 1, 0, a.spin_limit);
         }
         const int cnt = res.cnt;

@@ -187,15 +187,26 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
                 in.z[r] = e ? a.xyz[3 * (size_t)(e ? ir : 0) + 2] : 0.f;
             }
             const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
-            const RoundResult res = exchange_round<2>(L, a.exchange, G, w, 1, lane, round, in, npicked,
-                                                      cap, a.status, nullptr);
+            const RoundResult res = exchange_round<2, 2>(L, a.exchange, G, w, 1, lane, round, in,
+                                                            npicked, cap, a.status, nullptr, NW);
+            if (res.cnt < 0) {
+                // gave up before the replay: the other waves wait for it at two barriers
+                if (lane == 0) lds_write4(lds_offset(&L.team_total), 0u);
+                team_barrier();
+                team_barrier();
+            }
             if (lane == 0) {
                 s_cnt = res.cnt < 0 ? 0 : res.cnt;
                 if (res.cnt < 0) s_abort = 1;
             }
             if (w == 0 && res.cnt > 0) record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
+        } else {
+            // ---- 2b. help with the replay of the round ----
+            team_barrier();  // wave 0 has the candidates in place
+            team_matrix(L, lane, wave, NW);
+            team_barrier();  // masks complete
         }
-        __syncthreads();  // picks of this round visible to all waves
+        team_barrier();  // picks of this round visible to all waves
         if (s_abort) return;
         npicked += s_cnt;
     }

@@ -297,7 +297,7 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
         FFPS_STAMP(prof, 2);
         // a round of a cloud this small ends after a few tens of picks: about 64 live
         // candidates are enough, and the pairwise work grows with their square
-        const RoundResult res = replay_round<KC, true>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof,
+        const RoundResult res = replay_round<KC>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof,
                                                        NWK + 1, kSets, 64);
         // release the workers first, then note the picks
         if (lane == 0) {
