@@ -307,6 +307,23 @@ def main():
                              "unit": "GB/s", "frac": one["hbm_gbs_moved"] / HBM_PEAK_GBS,
                              "traffic": tr, "traffic_source": tr_src,
                              "kernel": "k_fps_stream, one pick per pass (64 passes over 32 Mi points)"}
+        # The streaming kernel forced onto the benchmark cloud, which is far too small
+        # for it (a pass is latency-bound there): reported because the regime question
+        # is asked of every configuration, not because it is the kernel to use.
+        ob4 = torch.empty((1, M1), dtype=torch.int32, device="cuda")
+        fb.ffps_exact(x, M1, 0, fb.FFPS_VARIANT_STREAM, workspace=ws, out=ob4)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fb.ffps_exact(x, M1, 0, fb.FFPS_VARIANT_STREAM, workspace=ws, out=ob4)
+        e1.record()
+        torch.cuda.synchronize()
+        ms4, passes4 = e0.elapsed_time(e1), fb.ffps_last_rounds(ws)
+        probe["config4_forced_onto_stream"] = {
+            "ms": ms4, "passes": passes4, "picks_per_pass": (M1 - 1) / passes4,
+            "hbm_gbs_moved": N * (BYTES_PER_UPDATE * passes4 - 4) / (ms4 * 1e-3) / 1e9,
+            "matches_register_resident_kernel": bool(torch.equal(ob4, out_exact)),
+        }
+        del ob4
         result["stream_probe"] = probe
         stream_ref = (xb.cpu().numpy()[0], m_big)
         del xb, wsb, ob
