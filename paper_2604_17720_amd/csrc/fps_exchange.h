@@ -322,7 +322,7 @@ __device__ __forceinline__ void lds_write2b(uint32_t off, uint32_t v) {
 // candidates a and a set of 64 candidates b, one per lane, and writes 16 bits of
 // each of b's masks: a before b; that and d <= T (picking a would put b out of
 // this round); that and d < value of b (picking a would lower b).  Bit 31 - (a mod 32) of 32-bit
-// word a / 32 stands for a.  Tasks are dealt out to the waves in turn.  Called by
+// word a / 32 stands for a.  Slices are dealt out to the waves in turn.  Called by
 // every wave between two workgroup barriers.
 __device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, int W) {
     const u32x2 hdr = lds_read8(lds_offset(&L.team_total));
@@ -331,15 +331,10 @@ __device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, in
     const uint32_t T = (uint32_t)__builtin_amdgcn_readfirstlane((int)hdr.y);
     const int nsl = (total + 15) >> 4, nsets = (total + kWave - 1) / kWave;
     const uint32_t mask_off = lds_offset(L.mask);
-    int sl = __builtin_amdgcn_readfirstlane(wv_in), set = 0;
-    while (true) {
-        while (sl >= nsl) { sl -= nsl; ++set; }
-        if (set >= nsets) break;
-        // Plain loads, all of a task's up front, so that they are in flight together.
-        // The arrays were written before the barrier.
-        const int b = set * kWave + lane;
-        const u32x4 cb = L.cand[b];
-        const u32x2 kb2 = L.key64[b];
+    // Plain loads, all of a task's up front, so that they are in flight together (the
+    // arrays were written before the barrier).  A wave takes slices wv, wv + W, ...
+    // and does all sets of a slice, whose 16 candidates it then reads only once.
+    for (int sl = __builtin_amdgcn_readfirstlane(wv_in); sl < nsl; sl += W) {
         u32x4 ra[16];
         u32x2 ka2[16];
 #pragma unroll
@@ -347,30 +342,35 @@ __device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, in
             ra[e] = L.cand[sl * 16 + e];  // the same address in all lanes
             ka2[e] = L.key64[sl * 16 + e];
         }
-        const float xb = u2f(cb.x), yb = u2f(cb.y), zb = u2f(cb.z);
-        const uint64_t kb = ((uint64_t)kb2.y << 32) | kb2.x;
-        uint32_t mk = 0u, ml = 0u, mb = 0u;
+#pragma unroll 1
+        for (int set = 0; set < nsets; ++set) {
+            const int b = set * kWave + lane;
+            const u32x4 cb = L.cand[b];
+            const u32x2 kb2 = L.key64[b];
+            const float xb = u2f(cb.x), yb = u2f(cb.y), zb = u2f(cb.z);
+            const uint64_t kb = ((uint64_t)kb2.y << 32) | kb2.x;
+            uint32_t mk = 0u, ml = 0u, mb = 0u;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const uint64_t ka = ((uint64_t)ka2[e].y << 32) | ka2[e].x;
-            const uint32_t d = f2u(sqdist(xb, yb, zb, u2f(ra[e].x), u2f(ra[e].y), u2f(ra[e].z)));
-            // a before b: the sign of the 64-bit difference of the keys (both below 2^63)
-            mb = __builtin_amdgcn_alignbit(mb, (uint32_t)((kb - ka) >> 32), 31);
-            // values are bit patterns of non-negative numbers: the sign of a difference is
-            // the comparison, and it goes into the mask (built from its most significant
-            // end: m = 2 m + bit) with one funnel shift
-            mk = __builtin_amdgcn_alignbit(mk, T - d, 31);        // T < d, turned round below
-            ml = __builtin_amdgcn_alignbit(ml, d - kb2.y, 31);    // d < value of b
+            for (int e = 0; e < 16; ++e) {
+                const uint64_t ka = ((uint64_t)ka2[e].y << 32) | ka2[e].x;
+                const uint32_t d = f2u(sqdist(xb, yb, zb, u2f(ra[e].x), u2f(ra[e].y), u2f(ra[e].z)));
+                // a before b: the sign of the 64-bit difference of the keys (both below 2^63)
+                mb = __builtin_amdgcn_alignbit(mb, (uint32_t)((kb - ka) >> 32), 31);
+                // values are bit patterns of non-negative numbers: the sign of a difference is
+                // the comparison, and it goes into the mask (built from its most significant
+                // end: m = 2 m + bit) with one funnel shift
+                mk = __builtin_amdgcn_alignbit(mk, T - d, 31);        // T < d, turned round below
+                ml = __builtin_amdgcn_alignbit(ml, d - kb2.y, 31);    // d < value of b
+            }
+            // the first two masks are only wanted where a comes before b
+            mk = ~mk & mb;
+            ml &= mb;
+            // two slices share a 32-bit word, the earlier one in its upper half
+            const uint32_t at = mask_off + (uint32_t)b * kMaskRow + (uint32_t)(sl ^ 1) * 2;
+            lds_write2b(at, mk);
+            lds_write2b(at + kMaskPlane, ml);
+            lds_write2b(at + 2 * kMaskPlane, mb);
         }
-        // the first two masks are only wanted where a comes before b
-        mk = ~mk & mb;
-        ml &= mb;
-        // two slices share a 32-bit word, the earlier one in its upper half
-        const uint32_t at = mask_off + (uint32_t)b * kMaskRow + (uint32_t)(sl ^ 1) * 2;
-        lds_write2b(at, mk);
-        lds_write2b(at + kMaskPlane, ml);
-        lds_write2b(at + 2 * kMaskPlane, mb);
-        sl += W;
     }
 }
 
