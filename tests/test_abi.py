@@ -85,6 +85,9 @@ def test_entry_points_validate_before_touching_the_device():
     assert exact(start=-1) == fb.FFPS_ERR_INVALID_ARG
     assert exact(start=100) == fb.FFPS_ERR_INVALID_ARG
     assert exact(variant=9) == fb.FFPS_ERR_INVALID_ARG
+    assert exact(variant=1 << 17) == fb.FFPS_ERR_INVALID_ARG      # above the picks cap and the test knob
+    assert exact(variant=-1) == fb.FFPS_ERR_INVALID_ARG
+    assert fb.FFPS_VARIANT_TEST_NO_WAIT == 1 << 16 and fb.variant_with_picks(2, 7) == 2 | (7 << 8)
     assert exact(wsb=ctypes.c_size_t(16)) == fb.FFPS_ERR_WORKSPACE_TOO_SMALL
 
     k = ctypes.c_int(-7)
