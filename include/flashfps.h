@@ -48,6 +48,7 @@ extern "C" {
 #define FFPS_ERR_LAUNCH_FAILED (-4)       /* a HIP call failed                                     */
 #define FFPS_ERR_TIMEOUT (-5)             /* a kernel gave up waiting for another workgroup        */
 #define FFPS_ERR_UNSUPPORTED_SIZE (-6)    /* the requested kernel variant cannot hold this N       */
+#define FFPS_ERR_INTERNAL (-7)            /* a kernel found its own intermediate results inconsistent */
 
 /* FPS-Prune switches (Alg. 1, layer 1). */
 #define FFPS_FLAG_CP 1u /* candidate pruning: FPS sees only N' = ceil(N * keep) points      */
@@ -203,8 +204,10 @@ int ffps_gather_rows(const float *d_rows, int B, int N, int C, const int32_t *d_
 /*
  * Status word the kernels of the last call on this workspace left behind:
  * synchronises `stream`, copies one int from the workspace and returns it
- * (FFPS_OK, or FFPS_ERR_TIMEOUT when a workgroup stopped waiting for another;
- * the outputs of that call are then undefined).
+ * (FFPS_OK; FFPS_ERR_TIMEOUT when a workgroup stopped waiting for another;
+ * FFPS_ERR_INTERNAL when a round of a multi-pick kernel named no pick, which
+ * the method rules out, and the kernel went on only in order to end; the
+ * outputs of such a call are undefined).
  */
 int ffps_last_status(const void *d_ws, void *stream);
 

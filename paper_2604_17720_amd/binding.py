@@ -18,6 +18,7 @@ FFPS_ERR_UNSUPPORTED_DEVICE = -3
 FFPS_ERR_LAUNCH_FAILED = -4
 FFPS_ERR_TIMEOUT = -5
 FFPS_ERR_UNSUPPORTED_SIZE = -6
+FFPS_ERR_INTERNAL = -7
 FFPS_FLAG_CP = 1
 FFPS_FLAG_IP = 2
 FFPS_FLAG_PERM = 4

@@ -9,6 +9,9 @@
 #include "../../include/flashfps.h"
 #include "fps_launch.h"
 
+static_assert(ffps::kErrGaveUp == FFPS_ERR_TIMEOUT && ffps::kErrInconsistent == FFPS_ERR_INTERNAL,
+              "the kernels write these codes into the status word");
+
 namespace {
 
 using namespace ffps;
@@ -251,6 +254,7 @@ const char *ffps_strerror(int code) {
         case FFPS_ERR_LAUNCH_FAILED: return "HIP call failed";
         case FFPS_ERR_TIMEOUT: return "a workgroup stopped waiting for another";
         case FFPS_ERR_UNSUPPORTED_SIZE: return "kernel variant cannot hold this cloud size";
+        case FFPS_ERR_INTERNAL: return "a kernel found its own intermediate results inconsistent";
         default: return "unknown error code";
     }
 }

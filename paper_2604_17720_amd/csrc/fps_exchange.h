@@ -384,6 +384,9 @@ __device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, in
 // candidate arrays are used up.
 struct RoundResult {
     int cnt;        // picks of the round, or -1 when the round failed
+    bool stuck;     // the pairwise masks named no pick at all, which cannot happen while
+                    // they are consistent; cnt is 1 then so that the kernel still ends,
+                    // and the caller reports kErrInconsistent in the status word
     bool by_lane;   // picks noted in the lanes (below) rather than in L.pk_idx / L.pk_val
     // by_lane: what this lane's live candidates became: pick number within the
     // round (-1: not picked), point index, value when picked
@@ -542,6 +545,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
     if (prof && ordered) prof->acc[total <= kWave ? 5 : 6] += 1;
 #endif
     RoundResult res;
+    res.stuck = false;
 #pragma unroll
     for (int s = 0; s < kSets; ++s) {
         res.pc[s] = -1;
@@ -756,6 +760,12 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             if (nsets == 1 || MAXS == 1) settle(std::integral_constant<int, 1>{});
             else if (nsets == 2 || MAXS == 2) settle(std::integral_constant<int, 2>{});
             else if constexpr (MAXS >= 3) settle(std::integral_constant<int, 3>{});
+            if (cnt == 0) {
+                // The first candidate of the order is always a pick.  Every round must
+                // make progress for the kernel to end, whatever went wrong.
+                cnt = 1;
+                res.stuck = true;
+            }
             FFPS_ORD(4);
             FFPS_SUB(3);
 #ifdef FFPS_PROFILE
@@ -793,6 +803,15 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
     res.cnt = cnt;
     res.by_lane = ordered;
     return res;
+}
+
+// Status word for a round whose masks named no pick (FFPS_ERR_INTERNAL of the C
+// interface, kErrInconsistent); status[2] = the round.  Called by one lane.
+__device__ __forceinline__ void note_inconsistent(int *status, int round) {
+    int expected = 0;
+    if (__hip_atomic_compare_exchange_strong(status, &expected, kErrInconsistent, __ATOMIC_RELAXED,
+                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        status[2] = round;
 }
 
 __device__ __forceinline__ void record_picks(const RoundLds &L, int lane, const RoundResult &r,
@@ -888,7 +907,7 @@ __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchang
         missing = (int)wave_min_u32((uint32_t)missing);
         if (lane == 0) {
             int expected = 0;
-            if (__hip_atomic_compare_exchange_strong(status, &expected, -5, __ATOMIC_RELAXED,
+            if (__hip_atomic_compare_exchange_strong(status, &expected, kErrGaveUp, __ATOMIC_RELAXED,
                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
                 status[2] = (int)round;
                 status[3] = missing;

@@ -291,6 +291,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             lds_write8(fin_off, f);
         }
         team_barrier();  // the workers wait here for the picks
+        if (res.stuck && lane == 0) note_inconsistent(a.status, (int)round);
         if (w == 0) record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
         npicked += cnt;
         FFPS_STAMP(prof, 4);

@@ -10,6 +10,10 @@ namespace ffps {
 #define FFPS_MAX_PICKS 192
 #endif
 constexpr int kMaxPicksPerRound = FFPS_MAX_PICKS;  // picks one round may deliver
+// Status words the kernels write themselves (the C interface's FFPS_ERR_TIMEOUT
+// and FFPS_ERR_INTERNAL).
+constexpr int kErrGaveUp = -5;
+constexpr int kErrInconsistent = -7;
 
 // ---- fps_wg.hip: one workgroup per cloud ------------------------------------
 int wg_capacity();   // largest N the single-workgroup kernels hold

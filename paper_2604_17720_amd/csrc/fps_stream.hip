@@ -199,6 +199,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_fps_stream(StreamArgs a) {
                 s_cnt = res.cnt < 0 ? 0 : res.cnt;
                 if (res.cnt < 0) s_abort = 1;
             }
+            if (res.cnt > 0 && res.stuck && lane == 0) note_inconsistent(a.status, (int)round);
             if (w == 0 && res.cnt > 0) record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
         } else {
             // ---- 2b. help with the replay of the round ----

@@ -306,6 +306,7 @@ __global__ __launch_bounds__(kWave *wgm_waves(NWK)) void k_fps_wgm(WgmArgs a) {
             lds_write8(fin_off, f);
         }
         team_barrier();  // the workers wait here for the picks
+        if (res.stuck && lane == 0) note_inconsistent(a.status, round);
         record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
         npicked += res.cnt;
         FFPS_STAMP(prof, 4);

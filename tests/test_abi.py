@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported():
 def test_version_and_error_strings():
     assert fb.ffps_version() >= 100
     seen = set()
-    for code in (0, -1, -2, -3, -4, -5, -6):
+    for code in (0, -1, -2, -3, -4, -5, -6, -7):
         s = fb.ffps_strerror(code)
         assert s and s not in seen
         seen.add(s)
