@@ -162,11 +162,11 @@ __device__ __forceinline__ u32x4 lds_read16(uint32_t off) {
     return r;
 }
 
-// The records of three candidates and their 8-byte keys, all reads in flight together.
-__device__ __forceinline__ void lds_read_own_keys(u32x4 (&c)[3], u32x2 (&k)[3], const uint32_t (&a_c)[3],
+// The records of three candidates and the complements of their indices, all reads in flight together.
+__device__ __forceinline__ void lds_read_own_keys(u32x4 (&c)[3], uint32_t (&k)[3], const uint32_t (&a_c)[3],
                                                   const uint32_t (&a_k)[3]) {
     asm volatile("ds_read_b128 %0, %6\n\tds_read_b128 %1, %7\n\tds_read_b128 %2, %8\n\t"
-                 "ds_read_b64 %3, %9\n\tds_read_b64 %4, %10\n\tds_read_b64 %5, %11\n\t"
+                 "ds_read_b32 %3, %9\n\tds_read_b32 %4, %10\n\tds_read_b32 %5, %11\n\t"
                  "s_waitcnt lgkmcnt(0)"
                  : "=&v"(c[0]), "=&v"(c[1]), "=&v"(c[2]), "=&v"(k[0]), "=&v"(k[1]), "=&v"(k[2])
                  : "v"(a_c[0]), "v"(a_c[1]), "v"(a_c[2]), "v"(a_k[0]), "v"(a_k[1]), "v"(a_k[2])
@@ -264,7 +264,7 @@ struct RoundLds {
     // lane, take what the compaction discards (one common entry would make every
     // such write a 64-way bank conflict)
     __attribute__((aligned(16))) u32x4 cand[kMaxLive + 4 + kWave];   // {x, y, z, value}
-    __attribute__((aligned(16))) u32x2 key64[kMaxLive + 4 + kWave];  // {complement of the index, value}: compares as the order does
+    __attribute__((aligned(16))) uint32_t nidx[kMaxLive + 4 + kWave];  // complement of the index: {value, nidx} compares as the order does
     // replay by the whole workgroup: number of live candidates (0: nothing to do this
     // round) and the threshold, then for every candidate b three bit masks over the
     // candidates a, in slices of 16: a lowers b to the threshold or below / a lowers b
@@ -314,7 +314,7 @@ __device__ __forceinline__ void lds_write2b(uint32_t off, uint32_t v) {
 // What the picks of a round do to each other, worked out by all W waves of a
 // workgroup (the wave that replays and the worker waves, which have nothing
 // else to do at that point).  L.cand[0 .. total) holds the live candidates
-// {x, y, z, value} in any order and L.key64 {complement of the index, value},
+// {x, y, z, value} in any order and L.nidx the complements of their indices,
 // followed by at least 15 entries of value 0.  For candidates a and b let d be their squared
 // distance (the individually rounded operations of sqdist, which give the same
 // bits either way round) and let "a before b" mean that a precedes b in the
@@ -331,45 +331,74 @@ __device__ __forceinline__ void team_matrix(RoundLds &L, int lane, int wv_in, in
     const uint32_t T = (uint32_t)__builtin_amdgcn_readfirstlane((int)hdr.y);
     const int nsl = (total + 15) >> 4, nsets = (total + kWave - 1) / kWave;
     const uint32_t mask_off = lds_offset(L.mask);
-    // Plain loads, all of a task's up front, so that they are in flight together (the
-    // arrays were written before the barrier).  A wave takes slices wv, wv + W, ...
-    // and does all sets of a slice, whose 16 candidates it then reads only once.
-    for (int sl = __builtin_amdgcn_readfirstlane(wv_in); sl < nsl; sl += W) {
-        u32x4 ra[16];
-        u32x2 ka2[16];
+    // One task: candidates a = 16 sl .. 16 sl + 15 (records ra, keys ka2; sl may differ
+    // from lane to lane) against candidate b of this lane.
+    auto task = [&](const u32x4 (&ra)[16], const u32x4 (&na)[4], int sl, int b, bool write) {
+        const u32x4 cb = L.cand[b];
+        const uint32_t nb = L.nidx[b];
+        const float xb = u2f(cb.x), yb = u2f(cb.y), zb = u2f(cb.z);
+        const uint64_t kb = ((uint64_t)cb.w << 32) | nb;
+        uint32_t mk = 0u, ml = 0u, mb = 0u;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            ra[e] = L.cand[sl * 16 + e];  // the same address in all lanes
-            ka2[e] = L.key64[sl * 16 + e];
+            const uint64_t ka = ((uint64_t)ra[e].w << 32) | na[e >> 2][e & 3];
+            const uint32_t d = f2u(sqdist(xb, yb, zb, u2f(ra[e].x), u2f(ra[e].y), u2f(ra[e].z)));
+            // a before b: the sign of the 64-bit difference of the keys (both below 2^63)
+            mb = __builtin_amdgcn_alignbit(mb, (uint32_t)((kb - ka) >> 32), 31);
+            // values are bit patterns of non-negative numbers: the sign of a difference is
+            // the comparison, and it goes into the mask (built from its most significant
+            // end: m = 2 m + bit) with one funnel shift
+            mk = __builtin_amdgcn_alignbit(mk, T - d, 31);        // T < d, turned round below
+            ml = __builtin_amdgcn_alignbit(ml, d - cb.w, 31);     // d < value of b
         }
-#pragma unroll 1
-        for (int set = 0; set < nsets; ++set) {
-            const int b = set * kWave + lane;
-            const u32x4 cb = L.cand[b];
-            const u32x2 kb2 = L.key64[b];
-            const float xb = u2f(cb.x), yb = u2f(cb.y), zb = u2f(cb.z);
-            const uint64_t kb = ((uint64_t)kb2.y << 32) | kb2.x;
-            uint32_t mk = 0u, ml = 0u, mb = 0u;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const uint64_t ka = ((uint64_t)ka2[e].y << 32) | ka2[e].x;
-                const uint32_t d = f2u(sqdist(xb, yb, zb, u2f(ra[e].x), u2f(ra[e].y), u2f(ra[e].z)));
-                // a before b: the sign of the 64-bit difference of the keys (both below 2^63)
-                mb = __builtin_amdgcn_alignbit(mb, (uint32_t)((kb - ka) >> 32), 31);
-                // values are bit patterns of non-negative numbers: the sign of a difference is
-                // the comparison, and it goes into the mask (built from its most significant
-                // end: m = 2 m + bit) with one funnel shift
-                mk = __builtin_amdgcn_alignbit(mk, T - d, 31);        // T < d, turned round below
-                ml = __builtin_amdgcn_alignbit(ml, d - kb2.y, 31);    // d < value of b
-            }
-            // the first two masks are only wanted where a comes before b
-            mk = ~mk & mb;
-            ml &= mb;
-            // two slices share a 32-bit word, the earlier one in its upper half
-            const uint32_t at = mask_off + (uint32_t)b * kMaskRow + (uint32_t)(sl ^ 1) * 2;
+        // the first two masks are only wanted where a comes before b
+        mk = ~mk & mb;
+        ml &= mb;
+        // two slices share a 32-bit word, the earlier one in its upper half
+        const uint32_t at = mask_off + (uint32_t)b * kMaskRow + (uint32_t)(sl ^ 1) * 2;
+        if (write) {
             lds_write2b(at, mk);
             lds_write2b(at + kMaskPlane, ml);
             lds_write2b(at + 2 * kMaskPlane, mb);
+        }
+    };
+    // When the last set holds no more than 16 (32) candidates, a task against it would
+    // leave three quarters (half) of the lanes idle: such a set is taken by groups of
+    // 4 (2) slices instead, each row of 16 (32) lanes with a slice of its own.
+    const int tail = total - (nsets - 1) * kWave;
+    const int pack = tail <= 16 ? 4 : tail <= 32 ? 2 : 1;
+    const int nmain = pack > 1 ? nsets - 1 : nsets;  // sets taken slice by slice
+    const int wv = __builtin_amdgcn_readfirstlane(wv_in);
+    // Plain loads, all of a task's up front, so that they are in flight together (the
+    // arrays were written before the barrier).  A wave takes slices wv, wv + W, ...
+    // and does all (full) sets of a slice, whose 16 candidates it then reads only once.
+    if (nmain > 0) {
+        for (int sl = wv; sl < nsl; sl += W) {
+            u32x4 ra[16], na[4];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) ra[e] = L.cand[sl * 16 + e];  // the same address in all lanes
+#pragma unroll
+            for (int e = 0; e < 4; ++e) na[e] = *reinterpret_cast<const u32x4 *>(&L.nidx[sl * 16 + 4 * e]);
+#pragma unroll 1
+            for (int set = 0; set < nmain; ++set) task(ra, na, sl, set * kWave + lane, true);
+        }
+    }
+    if (pack > 1) {
+        // groups of slices, dealt out from the last wave downwards (the first waves
+        // have the most slices above)
+        const int rows = kWave / pack, rsh = pack == 4 ? 4 : 5;  // lanes per slice, and its log2
+        const int ngroups = (nsl + pack - 1) / pack;
+#pragma unroll 1
+        for (int g = W - 1 - wv; g < ngroups; g += W) {
+            const int sl = g * pack + (lane >> rsh);
+            const bool ok = sl < nsl;
+            const int sr = ok ? sl : nsl - 1;
+            u32x4 ra[16], na[4];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) ra[e] = L.cand[sr * 16 + e];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) na[e] = *reinterpret_cast<const u32x4 *>(&L.nidx[sr * 16 + 4 * e]);
+            task(ra, na, sr, (nsets - 1) * kWave + (lane & (rows - 1)), ok);
         }
     }
 }
@@ -553,7 +582,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
         res.pv[s] = 0u;
     }
     if (ordered) {
-        const uint32_t cand_off = lds_offset(L.cand), key64_off = lds_offset(L.key64);
+        const uint32_t cand_off = lds_offset(L.cand), nidx_off = lds_offset(L.nidx);
         // compaction without branches: a candidate that is not live goes to the
         // lane's own slot behind the live ones, which nobody reads
         {
@@ -565,9 +594,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 u32x4 r;
                 r.x = f2u(cx[q]); r.y = f2u(cy[q]); r.z = f2u(cz[q]); r.w = cv[q];
                 lds_write16(cand_off + (live ? pos : dump) * 16, r);
-                u32x2 k2;
-                k2.x = ~ci[q]; k2.y = cv[q];
-                lds_write8(key64_off + (live ? pos : dump) * 8, k2);
+                lds_write4(nidx_off + (live ? pos : dump) * 4, ~ci[q]);
                 pos += live ? 1u : 0u;
             }
         }
@@ -586,14 +613,13 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             const int p = lane + s * kWave;
             h[s] = p < total;
             const uint32_t q = h[s] ? (uint32_t)p : 0u;
-            a_c[s] = cand_off + q * 16; a_k[s] = key64_off + q * 8;
+            a_c[s] = cand_off + q * 16; a_k[s] = nidx_off + q * 4;
         }
         u32x4 c[kSets];
-        u32x2 k2[kSets];
         uint32_t ix[kSets], o[kSets];  // index; value at the start of the round
-        lds_read_own_keys(c, k2, a_c, a_k);
+        lds_read_own_keys(c, ix, a_c, a_k);
 #pragma unroll
-        for (int s = 0; s < kSets; ++s) ix[s] = ~k2[s].x;
+        for (int s = 0; s < kSets; ++s) ix[s] = ~ix[s];
 #pragma unroll
         for (int s = 0; s < kSets; ++s) o[s] = h[s] ? c[s].w : 0u;
         FFPS_ORD(0);
@@ -614,9 +640,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 u32x4 zr;
                 zr.x = 0u; zr.y = 0u; zr.z = 0u; zr.w = 0u;
                 lds_write16(cand_off + (uint32_t)(total + lane) * 16, zr);
-                u32x2 z2;
-                z2.x = 0u; z2.y = 0u;
-                lds_write8(key64_off + (uint32_t)(total + lane) * 8, z2);
+                lds_write4(nidx_off + (uint32_t)(total + lane) * 4, 0u);
             }
             if (lane == 0) {
                 u32x2 hd;

@@ -145,10 +145,13 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
 #pragma unroll
                 for (int e = 0; e < 8; ++e) sl[e] = L.pk[c0 + e];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
+                for (int e = 0; e < 8; e += 2) {
                     const float lx = u2f(sl[e].x), ly = u2f(sl[e].y), lz = u2f(sl[e].z);
+                    const float kx = u2f(sl[e + 1].x), ky = u2f(sl[e + 1].y), kz = u2f(sl[e + 1].z);
 #pragma unroll
-                    for (int j = 0; j < P; ++j) m[j] = min_dist(m[j], sqdist(x[j], y[j], z[j], lx, ly, lz));
+                    for (int j = 0; j < P; ++j)
+                        m[j] = min3_dist(m[j], sqdist(x[j], y[j], z[j], lx, ly, lz),
+                                         sqdist(x[j], y[j], z[j], kx, ky, kz));
                 }
             }
             applied = upto;
