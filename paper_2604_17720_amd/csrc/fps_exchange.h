@@ -61,11 +61,13 @@ __host__ __device__ constexpr size_t buf_bytes(int T) { return chunks_of(T) * kC
 // A chunk is valid for a round when its last word equals this value.  Memory
 // cleared to zero never validates (the round term is non-zero for round >= 1),
 // a chunk of round-2 in the same buffer does not validate, and a read that
-// mixed old and new words fails the test and is simply polled again.
+// mixed old and new words (the hardware does not tear an aligned 16-byte access)
+// would pass only if the words it got wrong happened to leave the XOR unchanged;
+// it is simply polled again otherwise.  Kept to three instructions per chunk: the
+// gathering wave checks 24 chunks per lane on the critical path of every round.
 __device__ __forceinline__ uint32_t chunk_check(uint32_t a, uint32_t b, uint32_t c, uint32_t round,
                                                 uint32_t which) {
-    uint32_t m = a ^ ((b << 11) | (b >> 21)) ^ ((c << 22) | (c >> 10));
-    return m ^ (round * 0x9E3779B1u + which * 0x85EBCA6Bu);
+    return a ^ b ^ c ^ (round * 0x9E3779B1u + which * 0x85EBCA6Bu);
 }
 __device__ __forceinline__ bool chunk_ok(const u32x4 &c, uint32_t round, uint32_t which) {
     return c.w == chunk_check(c.x, c.y, c.z, round, which);
@@ -583,8 +585,9 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
     }
     if (ordered) {
         const uint32_t cand_off = lds_offset(L.cand), nidx_off = lds_offset(L.nidx);
-        // compaction without branches: a candidate that is not live goes to the
-        // lane's own slot behind the live ones, which nobody reads
+        // compaction without branches (predicated writes by the live lanes alone were
+        // slower): a candidate that is not live goes to the lane's own slot behind the
+        // live ones, which nobody reads
         {
             const uint32_t dump = (uint32_t)(kMaxLive + 4 + lane);
             uint32_t pos = (uint32_t)before;

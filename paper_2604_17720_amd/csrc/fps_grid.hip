@@ -256,13 +256,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             for (int r = 0; r < kT; ++r) {
                 in.v[r] = g3.v[r]; in.i[r] = g3.i[r];
                 const WaveTop &o = wtop[src[r]];  // entry r is wave src[r]'s ent[r]-th
-                in.x[r] = o.x[0]; in.y[r] = o.y[0]; in.z[r] = o.z[0];
-#pragma unroll
-                for (int e = 1; e < kT; ++e) {
-                    in.x[r] = ent[r] == e ? o.x[e] : in.x[r];
-                    in.y[r] = ent[r] == e ? o.y[e] : in.y[r];
-                    in.z[r] = ent[r] == e ? o.z[e] : in.z[r];
-                }
+                in.x[r] = o.x[ent[r]]; in.y[r] = o.y[ent[r]]; in.z[r] = o.z[ent[r]];
             }
             in.bound = g3.v[kT];
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
