@@ -249,7 +249,8 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             // ---- 2a. the workgroup's kT best + bound from the worker waves' ----
             const bool act = lane < NWK;
             int src[kT], ent[kT];
-            const TopK<kT> g3 = merge_topk<kT>(wtop[act ? lane : 0].t, act, lane,
+            const TopK<kT> own = wtop[act ? lane : 0].t;  // a copy: all its words are read at once, before the merge
+            const TopK<kT> g3 = merge_topk<kT>(own, act, lane,
                                                [](uint32_t v) { return row_max_uniform(v); },
                                                [](uint32_t v) { return row_min_uniform(v); }, src, ent);
 #pragma unroll
