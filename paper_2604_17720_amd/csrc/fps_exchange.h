@@ -535,7 +535,20 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
             }
         };
         count_live();
-        if (total > live_sets * kWave) {
+        // about `aim` candidates, taking their values as evenly spread between the
+        // threshold and the best one (any threshold above the bound will do)
+        auto thin_out = [&](int aim) {
+            const uint32_t span = V - T;
+            T = V - (uint32_t)(((uint64_t)span * (uint32_t)aim) / (uint32_t)total);
+            count_live();
+        };
+        if (live_target > 0 && total > live_target + live_target / 4) thin_out(live_target);
+        // more than fit: aim a little below the limit, twice if need be, before falling
+        // back on a threshold that is certain to fit but usually leaves far fewer
+        const int limit = live_sets * kWave;
+        if (total > limit) thin_out(limit - limit / 16);
+        if (total > limit) thin_out(limit - limit / 16);
+        if (total > limit) {
             // the largest value that is only number live_sets + 1 in its lane
             uint32_t t[kSets + 1] = {};
 #pragma unroll
@@ -545,15 +558,8 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                 for (int r = kSets; r >= 1; --r) t[r] = umax(t[r], v < t[r - 1] ? v : t[r - 1]);
                 t[0] = umax(t[0], v);
             }
-            T = umax(Bound, wave_max_u32(live_sets == 1 ? t[1] : live_sets == 2 ? t[2] : t[kSets]));
+            T = umax(T, wave_max_u32(live_sets == 1 ? t[1] : live_sets == 2 ? t[2] : t[kSets]));
             static_assert(MAXS >= 1 && MAXS <= kSets, "sets of 64 live candidates");
-            count_live();
-        }
-        if (live_target > 0 && total > live_target + live_target / 4) {
-            // about live_target candidates, taking their values as evenly spread between
-            // the threshold and the best one (any threshold above the bound will do)
-            const uint32_t span = V - T;
-            T = V - (uint32_t)(((uint64_t)span * (uint32_t)live_target) / (uint32_t)total);
             count_live();
         }
     }
