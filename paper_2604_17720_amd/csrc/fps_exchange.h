@@ -445,7 +445,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
                                             uint32_t (&ci)[KC], float (&cx)[KC], float (&cy)[KC],
                                             float (&cz)[KC], uint32_t lb, int npicked, int cap,
                                             RoundProf *prof, int team_waves, int live_sets = MAXS,
-                                            int live_target = 0) {
+                                            int live_target = 0, bool fresh = true) {
     const uint32_t pk_off = lds_offset(L.pk);
 #ifdef FFPS_PROFILE
     uint64_t sc = clock64();
@@ -516,7 +516,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
     uint32_t T = Bound;
     int total = 0, before = 0;
     FFPS_SUB(0);
-    if (V > Bound && cap > 1) {
+    if (V > Bound && (cap > 1 || !fresh)) {
         // total = live candidates of the wave, before = those of lower lanes: the
         // per-lane count goes through one ballot per bit of it
         auto count_live = [&]() {
@@ -817,7 +817,11 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
         if (lane == 0) lds_write4(lds_offset(&L.team_total), 0u);
         team_barrier();
         team_barrier();
-        while (true) {
+        // Not fresh: the candidates' values are exact but the caller cannot promise that
+        // the best point of all is among them, so nothing may be picked on the strength
+        // of being the best candidate alone.  The round is empty (cnt = 0) and the
+        // caller sees to it that the next one is fresh.
+        while (fresh) {
             uint32_t bv, bi;
             int bq;
             lane_best(bv, bi, bq);
@@ -878,7 +882,8 @@ __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchang
                                                       int nsub, int lane, uint32_t round,
                                                       const RoundInput<T> &in, int npicked, int cap,
                                                       int *status, RoundProf *prof, int team_waves,
-                                                      int live_target = 0, int spin_limit = kSpinLimit) {
+                                                      int live_target = 0, int spin_limit = kSpinLimit,
+                                                      bool fresh = true) {
     static_assert(T == 2 || T == 3, "two or three candidates per unit");
     constexpr int NCH = chunks_of(T);
     constexpr int KC = T * kRPL;  // candidates per lane before compaction
@@ -971,7 +976,7 @@ __device__ __forceinline__ RoundResult exchange_round(RoundLds &L, char *exchang
         lb = umax(lb, present ? bnd : 0u);
     }
     return replay_round<KC, MAXS>(L, lane, cv, ci, cx, cy, cz, lb, npicked, cap, prof, team_waves, MAXS,
-                                        live_target);
+                                        live_target, fresh);
 }
 
 }  // namespace ffps

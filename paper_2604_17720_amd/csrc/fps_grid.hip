@@ -63,7 +63,9 @@ __host__ __device__ constexpr int grid_waves(int nwk) { return nwk + 1; }
 template <int NWK, int P>
 __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_in) {
     static_assert(NWK == 3 || NWK == 7, "four or eight waves in all");
-    __shared__ WaveTop wtop[NWK];
+    // reports of the worker waves, two buffers: the communication wave reads one while the
+    // workers fill the other
+    __shared__ WaveTop wtop[2][NWK];
     __shared__ RoundLds L;
     // {batch id, picks emitted in total once that batch is complete}, one 8-byte word
     __shared__ __attribute__((aligned(8))) uint32_t fin[2];
@@ -132,14 +134,20 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             m[j] = ok ? __builtin_inff() : 0.f;
         }
         int applied = 0;  // picks applied so far
+        int buf = 1;      // buffer that holds this wave's last report
+        bool first = true;
         for (;;) {
-            // ---- 1a. the picks of the round (first the seed point), which are all in
-            //      place by now: {round, picks so far} says how many.  Eight slots per
-            //      step; the slots behind the last pick of the round hold picks of
-            //      earlier rounds (or the seed point), which every value reflects
-            //      already, so applying those again changes nothing. ----
+            // {round, picks so far}: the picks of the last round are all in L.pk by now
             const u32x2 f = lds_read8(fin_off);
             const int upto = __builtin_amdgcn_readfirstlane((int)f.y);
+            if (s_abort || upto >= a.M) break;  // the picks of the last round need not be applied
+            if (upto > applied) {
+            // ---- 1a. the picks of the round (first the seed point).  Eight slots per
+            //      step; the slots behind the last pick of the round hold picks of
+            //      earlier rounds (or the seed point), which every value reflects
+            //      already, so applying those again changes nothing.  Meanwhile the
+            //      communication wave is already at work on the next round: it brings
+            //      this wave's previous report up to date itself. ----
             for (int c0 = 0; c0 < upto - applied; c0 += 8) {
                 u32x4 sl[8];
 #pragma unroll
@@ -155,7 +163,6 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
                 }
             }
             applied = upto;
-            if (s_abort || applied >= a.M) break;
             // ---- 1b. the lane's kT + 1 largest values (element numbers for the first kT) ----
             float top[kT + 1];
             int tj[kT];
@@ -195,17 +202,22 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
                 for (int e = 1; e < kT; ++e) ej = ent[r] == e ? tj[e] : ej;
                 pick_xyz<P>(x, y, z, readlane_i(ej, src[r]), src[r], wx[r], wy[r], wz[r]);
             }
+            buf ^= 1;
             if (lane == 0) {
-                WaveTop &o = wtop[wk];
+                WaveTop &o = wtop[buf][wk];
                 o.t = wt;
 #pragma unroll
                 for (int r = 0; r < kT; ++r) {
                     o.x[r] = wx[r]; o.y[r] = wy[r]; o.z[r] = wz[r];
                 }
             }
-            __syncthreads();  // wave tops ready for the communication wave
-            // ---- 1d. help with the replay of the next round ----
-            team_barrier();  // the communication wave has the candidates in place
+            }  // picks applied, report made
+            if (first) {
+                __syncthreads();  // the first report is in place before the communication wave reads it
+                first = false;
+            }
+            // ---- 1d. help with the replay of the round ----
+            team_barrier();  // the communication wave has the candidates in place, every report is made
             team_matrix(L, lane, wave, NWK + 1);
             team_barrier();  // masks complete
             team_barrier();  // picks of the round in place
@@ -225,44 +237,116 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
     prof_store.last = wall_clock64();
     const uint64_t prof_w0 = prof_store.last, prof_c0 = clock64();
 #endif
+    // A round's report is not made by the workers: while they apply the picks of the
+    // round before (pend of them, in L.pk) and make their next report, this wave takes
+    // their previous one (buffer cur), applies those picks to its 3 NWK candidates
+    // itself and goes on to publish, gather and compact.  The candidates' values are
+    // exact that way; the bounds (each wave's fourth value) are one round old, which
+    // only makes them larger than need be.  What the stale report cannot promise is
+    // that the best point of all is a candidate: a round in which no candidate is
+    // above the bounds makes no pick then (replay_round, fresh = false), and the next
+    // one starts from reports that reflect every pick.
+    int cur = 0, pend = 0;
+    if (a.M > 1) __syncthreads();  // the workers' first report (the seed point applied) is in place
+    constexpr int NG = kWave / NWK;  // lanes per worker wave: each takes every NG-th pick
+    const int cs = lane % NWK, cg = lane / NWK < NG ? lane / NWK : NG - 1;
     while (npicked < a.M) {
         ++round;
         FFPS_STAMP(prof, 0);
-        __syncthreads();  // workers have applied every pick so far and filled wtop
+        // ---- 2a. the report of worker wave cs, brought up to date ----
+        uint32_t cv[kT], ci[kT], cbound;
+        float cx[kT], cy[kT], cz[kT];
+        {
+            const WaveTop o = wtop[cur][cs];
+#pragma unroll
+            for (int r = 0; r < kT; ++r) {
+                cv[r] = o.t.v[r]; ci[r] = o.t.i[r];
+                cx[r] = o.x[r]; cy[r] = o.y[r]; cz[r] = o.z[r];
+            }
+            cbound = o.t.v[kT];
+        }
+        if (pend > 0) {
+            float fv[kT];
+#pragma unroll
+            for (int r = 0; r < kT; ++r) fv[r] = u2f(cv[r]);
+            for (int c0 = 0; c0 < pend; c0 += 2 * NG) {
+                // a slot beyond the picks of the round: take slot 0, which is one of them
+                const int ca = c0 + cg, cb = c0 + NG + cg;
+                const u32x4 pa = L.pk[ca < pend ? ca : 0], pb = L.pk[cb < pend ? cb : 0];
+#pragma unroll
+                for (int r = 0; r < kT; ++r)
+                    fv[r] = min3_dist(fv[r], sqdist(cx[r], cy[r], cz[r], u2f(pa.x), u2f(pa.y), u2f(pa.z)),
+                                      sqdist(cx[r], cy[r], cz[r], u2f(pb.x), u2f(pb.y), u2f(pb.z)));
+            }
+            // the smallest over the NG lanes of a wave, in all of them
+#pragma unroll
+            for (int r = 0; r < kT; ++r) {
+                float acc = fv[r];
+#pragma unroll
+                for (int gg = 0; gg < NG; ++gg)
+                    acc = min_dist(acc, u2f((uint32_t)__builtin_amdgcn_ds_bpermute((cs + NWK * gg) * 4, (int)f2u(fv[r]))));
+                cv[r] = f2u(acc);
+            }
+        }
         FFPS_STAMP(prof, 1);
         RoundInput<kT> in;
         RoundResult res;
         const int cap = __builtin_amdgcn_readfirstlane(min(a.max_picks, a.M - npicked));
+        const bool fresh = pend == 0;
         if (a.wave_units) {
-            // ---- 2a. every worker wave is a unit of its own: lane s reports wave s ----
-            const WaveTop &o = wtop[lane < NWK ? lane : 0];
+            // ---- 2a'. every worker wave is a unit of its own: lane s reports wave s ----
 #pragma unroll
             for (int r = 0; r < kT; ++r) {
-                in.v[r] = o.t.v[r]; in.i[r] = o.t.i[r];
-                in.x[r] = o.x[r]; in.y[r] = o.y[r]; in.z[r] = o.z[r];
+                in.v[r] = cv[r]; in.i[r] = ci[r];
+                in.x[r] = cx[r]; in.y[r] = cy[r]; in.z[r] = cz[r];
             }
-            in.bound = o.t.v[kT];
+            in.bound = cbound;
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
             res = exchange_round<kT>(L, a.exchange, G * NWK, w * NWK, NWK, lane, round, in, npicked,
-                                           cap, a.status, prof, NWK + 1, 0, a.spin_limit);
+                                           cap, a.status, prof, NWK + 1, 0, a.spin_limit, fresh);
         } else {
-            // ---- 2a. the workgroup's kT best + bound from the worker waves' ----
+            // ---- 2a'. the workgroup's kT best + bound from the worker waves'.  The values
+            //      have changed, so each wave's three go back into order first (value
+            //      descending, index ascending). ----
+            static_assert(kT == 3, "a sorting network for three");
+            auto exchange = [&](int p, int q) {
+                const bool sw = cv[q] > cv[p] || (cv[q] == cv[p] && ci[q] < ci[p]);
+                const uint32_t tv = cv[p], ti = ci[p];
+                const float tx = cx[p], ty = cy[p], tz = cz[p];
+                cv[p] = sw ? cv[q] : tv; ci[p] = sw ? ci[q] : ti;
+                cx[p] = sw ? cx[q] : tx; cy[p] = sw ? cy[q] : ty; cz[p] = sw ? cz[q] : tz;
+                cv[q] = sw ? tv : cv[q]; ci[q] = sw ? ti : ci[q];
+                cx[q] = sw ? tx : cx[q]; cy[q] = sw ? ty : cy[q]; cz[q] = sw ? tz : cz[q];
+            };
+            exchange(0, 1); exchange(1, 2); exchange(0, 1);
             const bool act = lane < NWK;
             int src[kT], ent[kT];
-            const TopK<kT> own = wtop[act ? lane : 0].t;  // a copy: all its words are read at once, before the merge
+            TopK<kT> own;
+#pragma unroll
+            for (int r = 0; r < kT; ++r) {
+                own.v[r] = cv[r]; own.i[r] = ci[r];
+            }
+            own.v[kT] = cbound;
             const TopK<kT> g3 = merge_topk<kT>(own, act, lane,
                                                [](uint32_t v) { return row_max_uniform(v); },
                                                [](uint32_t v) { return row_min_uniform(v); }, src, ent);
 #pragma unroll
             for (int r = 0; r < kT; ++r) {
                 in.v[r] = g3.v[r]; in.i[r] = g3.i[r];
-                const WaveTop &o = wtop[src[r]];  // entry r is wave src[r]'s ent[r]-th
-                in.x[r] = o.x[ent[r]]; in.y[r] = o.y[ent[r]]; in.z[r] = o.z[ent[r]];
+                // entry r is wave src[r]'s ent[r]-th
+                const float ex = ent[r] == 0 ? cx[0] : ent[r] == 1 ? cx[1] : cx[2];
+                const float ey = ent[r] == 0 ? cy[0] : ent[r] == 1 ? cy[1] : cy[2];
+                const float ez = ent[r] == 0 ? cz[0] : ent[r] == 1 ? cz[1] : cz[2];
+                in.x[r] = u2f((uint32_t)readlane_i((int)f2u(ex), src[r]));
+                in.y[r] = u2f((uint32_t)readlane_i((int)f2u(ey), src[r]));
+                in.z[r] = u2f((uint32_t)readlane_i((int)f2u(ez), src[r]));
             }
-            in.bound = g3.v[kT];
+            // what is left of the lists, and every wave's own (older) bound, which a
+            // wave whose candidates are not used up keeps behind them
+            in.bound = umax(g3.v[kT], row_max_uniform(act ? cbound : 0u));
             // ---- 2b/2c/3. publish, gather, replay (picks go to L.pk as they are found) ----
             res = exchange_round<kT>(L, a.exchange, G, w, 1, lane, round, in, npicked, cap,
-                                           a.status, prof, NWK + 1, 0, a.spin_limit);
+                                           a.status, prof, NWK + 1, 0, a.spin_limit, fresh);
         }
         const int cnt = res.cnt;
         if (cnt < 0) {
@@ -292,6 +376,8 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         if (res.stuck && lane == 0) note_inconsistent(a.status, (int)round);
         if (w == 0) record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
         npicked += cnt;
+        if (pend > 0) cur ^= 1;  // the workers have made a new report meanwhile
+        pend = cnt;
         FFPS_STAMP(prof, 4);
     }
     if (w == 0 && lane == 0) {
