@@ -60,6 +60,7 @@ __device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
 }
 
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 
 // Unsigned max over each row of 16 lanes; the result is in lanes 15, 31, 47, 63.
 __device__ __forceinline__ uint32_t row16_max_u32(uint32_t v) {

@@ -516,7 +516,7 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
     uint32_t T = Bound;
     int total = 0, before = 0;
     FFPS_SUB(0);
-    if (V > Bound && (cap > 1 || !fresh)) {
+    if (V > Bound && cap > 1) {
         // total = live candidates of the wave, before = those of lower lanes: the
         // per-lane count goes through one ballot per bit of it
         auto count_live = [&]() {
@@ -819,14 +819,15 @@ __device__ __forceinline__ RoundResult replay_round(RoundLds &L, int lane, uint3
         team_barrier();
         // Not fresh: the candidates' values are exact but the caller cannot promise that
         // the best point of all is among them, so nothing may be picked on the strength
-        // of being the best candidate alone.  The round is empty (cnt = 0) and the
-        // caller sees to it that the next one is fresh.
-        while (fresh) {
+        // of being the best candidate alone: the first pick, too, must be above the
+        // bound.  If it is not the round is empty (cnt = 0) and the caller sees to it
+        // that the next one is fresh.
+        while (true) {
             uint32_t bv, bi;
             int bq;
             lane_best(bv, bi, bq);
             V = wave_max_u32(bv);
-            if (cnt > 0 && !(V > Bound)) break;
+            if ((cnt > 0 || !fresh) && !(V > Bound)) break;
             pl = best_lane(bv, bi, V, wmin);
             const int pq = readlane_i(bq, pl);
             pick_xyz<KC>(cx, cy, cz, pq, pl, px, py, pz);

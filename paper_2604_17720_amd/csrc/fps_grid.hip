@@ -66,6 +66,8 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
     // reports of the worker waves, two buffers: the communication wave reads one while the
     // workers fill the other
     __shared__ WaveTop wtop[2][NWK];
+    // the values of a report's kT candidates after the picks of the round that followed it
+    __shared__ uint32_t wupd[NWK][kT];
     __shared__ RoundLds L;
     // {batch id, picks emitted in total once that batch is complete}, one 8-byte word
     __shared__ __attribute__((aligned(8))) uint32_t fin[2];
@@ -142,6 +144,33 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             const int upto = __builtin_amdgcn_readfirstlane((int)f.y);
             if (s_abort || upto >= a.M) break;  // the picks of the last round need not be applied
             if (upto > applied) {
+            if (!first) {
+                // ---- 1z. first of all, what those picks do to the kT points of this wave's
+                //      last report (a few picks per lane), for the communication wave, which
+                //      builds the next round on them while the rest of this wave's points
+                //      follow ----
+                const WaveTop &o = wtop[buf][wk];
+                float qx[kT], qy[kT], qz[kT];
+                uint32_t qv[kT];
+#pragma unroll
+                for (int r = 0; r < kT; ++r) {
+                    qx[r] = o.x[r]; qy[r] = o.y[r]; qz[r] = o.z[r];
+                    qv[r] = lane == 0 ? o.t.v[r] : 0xffffffffu;
+                }
+                for (int c = lane; c < upto - applied; c += kWave) {
+                    const u32x4 pk = L.pk[c];
+#pragma unroll
+                    for (int r = 0; r < kT; ++r)
+                        qv[r] = umin(qv[r], f2u(sqdist(qx[r], qy[r], qz[r], u2f(pk.x), u2f(pk.y), u2f(pk.z))));
+                }
+#pragma unroll
+                for (int r = 0; r < kT; ++r) qv[r] = wave_min_u32(qv[r]);
+                if (lane == 0) {
+#pragma unroll
+                    for (int r = 0; r < kT; ++r) wupd[wk][r] = qv[r];
+                }
+                team_barrier();  // the communication wave waits here for all worker waves' updates
+            }
             // ---- 1a. the picks of the round (first the seed point).  Eight slots per
             //      step; the slots behind the last pick of the round hold picks of
             //      earlier rounds (or the seed point), which every value reflects
@@ -237,19 +266,19 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
     prof_store.last = wall_clock64();
     const uint64_t prof_w0 = prof_store.last, prof_c0 = clock64();
 #endif
-    // A round's report is not made by the workers: while they apply the picks of the
-    // round before (pend of them, in L.pk) and make their next report, this wave takes
-    // their previous one (buffer cur), applies those picks to its 3 NWK candidates
-    // itself and goes on to publish, gather and compact.  The candidates' values are
-    // exact that way; the bounds (each wave's fourth value) are one round old, which
-    // only makes them larger than need be.  What the stale report cannot promise is
-    // that the best point of all is a candidate: a round in which no candidate is
-    // above the bounds makes no pick then (replay_round, fresh = false), and the next
-    // one starts from reports that reflect every pick.
+    // The rounds overlap.  When a round's picks are in L.pk the workers first work out
+    // what they do to the kT points of their own last report (buffer cur), which takes
+    // a few picks per lane, and then apply them to all their points and make their next
+    // report.  Meanwhile this wave builds the next round on the updated last reports:
+    // merge, publish, gather, compaction.  The candidates' values are exact that way;
+    // the bounds (each wave's fourth value) are one round old, which only makes them
+    // larger than need be.  What such a report cannot promise is that the best point of
+    // all is a candidate: a round in which no candidate is above the bounds makes no
+    // pick then (replay_round, fresh = false), and the next one starts from reports
+    // that reflect every pick.
     int cur = 0, pend = 0;
     if (a.M > 1) __syncthreads();  // the workers' first report (the seed point applied) is in place
-    constexpr int NG = kWave / NWK;  // lanes per worker wave: each takes every NG-th pick
-    const int cs = lane % NWK, cg = lane / NWK < NG ? lane / NWK : NG - 1;
+    const int cs = lane % NWK;  // the worker wave whose report this lane holds
     while (npicked < a.M) {
         ++round;
         FFPS_STAMP(prof, 0);
@@ -266,27 +295,10 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             cbound = o.t.v[kT];
         }
         if (pend > 0) {
-            float fv[kT];
+            // the workers work out first what the pending picks do to these candidates
+            team_barrier();
 #pragma unroll
-            for (int r = 0; r < kT; ++r) fv[r] = u2f(cv[r]);
-            for (int c0 = 0; c0 < pend; c0 += 2 * NG) {
-                // a slot beyond the picks of the round: take slot 0, which is one of them
-                const int ca = c0 + cg, cb = c0 + NG + cg;
-                const u32x4 pa = L.pk[ca < pend ? ca : 0], pb = L.pk[cb < pend ? cb : 0];
-#pragma unroll
-                for (int r = 0; r < kT; ++r)
-                    fv[r] = min3_dist(fv[r], sqdist(cx[r], cy[r], cz[r], u2f(pa.x), u2f(pa.y), u2f(pa.z)),
-                                      sqdist(cx[r], cy[r], cz[r], u2f(pb.x), u2f(pb.y), u2f(pb.z)));
-            }
-            // the smallest over the NG lanes of a wave, in all of them
-#pragma unroll
-            for (int r = 0; r < kT; ++r) {
-                float acc = fv[r];
-#pragma unroll
-                for (int gg = 0; gg < NG; ++gg)
-                    acc = min_dist(acc, u2f((uint32_t)__builtin_amdgcn_ds_bpermute((cs + NWK * gg) * 4, (int)f2u(fv[r]))));
-                cv[r] = f2u(acc);
-            }
+            for (int r = 0; r < kT; ++r) cv[r] = wupd[cs][r];
         }
         FFPS_STAMP(prof, 1);
         RoundInput<kT> in;
