@@ -46,6 +46,7 @@ struct GridArgs {  // pointers are those of the first cloud of the launch
     const int *start_dev;  // per-cloud start indices overriding `start`, or null
     int wg_per_cloud;  // the grid holds (clouds of this launch) x wg_per_cloud workgroups
     int wave_units;    // 1: every worker wave reports on its own; 0: the workgroup reports as one
+    int overlap;       // 1: a round is built while the picks of the one before are applied; 0: after
     int32_t *idx_out;
     long idx_stride;   // elements between the outputs of consecutive clouds
     float *md_out;
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
             const int upto = __builtin_amdgcn_readfirstlane((int)f.y);
             if (s_abort || upto >= a.M) break;  // the picks of the last round need not be applied
             if (upto > applied) {
-            if (!first) {
+            if (!first && a.overlap) {
                 // ---- 1z. first of all, what those picks do to the kT points of this wave's
                 //      last report (a few picks per lane), for the communication wave, which
                 //      builds the next round on them while the rest of this wave's points
@@ -231,7 +232,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
                 for (int e = 1; e < kT; ++e) ej = ent[r] == e ? tj[e] : ej;
                 pick_xyz<P>(x, y, z, readlane_i(ej, src[r]), src[r], wx[r], wy[r], wz[r]);
             }
-            buf ^= 1;
+            buf = a.overlap ? buf ^ 1 : 0;
             if (lane == 0) {
                 WaveTop &o = wtop[buf][wk];
                 o.t = wt;
@@ -241,8 +242,10 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
                 }
             }
             }  // picks applied, report made
-            if (first) {
-                __syncthreads();  // the first report is in place before the communication wave reads it
+            if (first || !a.overlap) {
+                // the first report (without overlap: every report) is in place before the
+                // communication wave reads it
+                __syncthreads();
                 first = false;
             }
             // ---- 1d. help with the replay of the round ----
@@ -277,11 +280,12 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
     // pick then (replay_round, fresh = false), and the next one starts from reports
     // that reflect every pick.
     int cur = 0, pend = 0;
-    if (a.M > 1) __syncthreads();  // the workers' first report (the seed point applied) is in place
+    if (a.M > 1 && a.overlap) __syncthreads();  // the workers' first report (the seed point applied) is in place
     const int cs = lane % NWK;  // the worker wave whose report this lane holds
     while (npicked < a.M) {
         ++round;
         FFPS_STAMP(prof, 0);
+        if (!a.overlap) __syncthreads();  // the workers have applied every pick so far and made their reports
         // ---- 2a. the report of worker wave cs, brought up to date ----
         uint32_t cv[kT], ci[kT], cbound;
         float cx[kT], cy[kT], cz[kT];
@@ -389,7 +393,7 @@ __global__ __launch_bounds__(kWave *grid_waves(NWK)) void k_fps_grid(GridArgs a_
         if (w == 0) record_picks(L, lane, res, npicked, a.idx_out, a.md_out);
         npicked += cnt;
         if (pend > 0) cur ^= 1;  // the workers have made a new report meanwhile
-        pend = cnt;
+        pend = a.overlap ? cnt : 0;
         FFPS_STAMP(prof, 4);
     }
     if (w == 0 && lane == 0) {
@@ -500,6 +504,10 @@ hipError_t launch_fps_grid(const float *xyz, int clouds, int N, int M, int start
     const int per_wg = (N + G - 1) / G;  // most points any workgroup holds
     const int num_wg = clouds * G;
     a.wave_units = units_of(N, G) > G ? 1 : 0;
+    // Rounds of small clouds (every wave a unit) deliver few picks, and applying them is
+    // short work: nothing to hide a round's exchange behind, and reports that are one
+    // round old cost picks.  Those launches take one round after the other.
+    a.overlap = a.wave_units ? 0 : 1;
 #define X(NWK, P) \
     if (per_wg <= (NWK) * kWave * (P)) return launch_t<NWK, P>(a, num_wg, s);
     FFPS_GRID_SHAPES(X)

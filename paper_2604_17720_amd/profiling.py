@@ -27,7 +27,9 @@ import os
 import re
 import sys
 
-PHASES = ["loop top", "wait for the workers", "merge + publish", "gather (poll for all records)", "replay"]
+PHASES = ["loop top (outputs of the round before)", "wait for the workers' update of their last reports",
+          "merge + publish", "gather (poll for all records)",
+          "replay (count, compaction, wait for the workers, masks, settling)"]
 
 
 def _phases(args) -> None:
@@ -46,8 +48,10 @@ def _phases(args) -> None:
     print("Command: `python -m paper_2604_17720_amd.profiling phases` after "
           "`python -m paper_2604_17720_amd.build --profile`.")
     print("Times are those of workgroup 0's communication wave (100 MHz wall clock), per round; cycles are "
-          "shader cycles.\nThe instrumentation itself costs about 10 % (compare the kernel time below with "
-          "bench.py's).\n")
+          "shader cycles.\nThe workers apply the picks of the round before and make their next report while "
+          "this wave is between `loop top` and the first barrier of the replay, so the wait at that barrier is "
+          "what their path is longer by.\nThe instrumentation itself costs a few per cent (compare the kernel "
+          "time below with bench.py's).\n")
     for picks, M in ((1, 4001), (16, 20000), (0, 50000)):
         var = fb.variant_with_picks(fb.FFPS_VARIANT_GRID, picks)
         fb.ffps_exact(x4, M, 0, var, workspace=ws)
@@ -71,13 +75,13 @@ def _phases(args) -> None:
         print(f"- polls per gather: {st[15] / r:.2f}")
         print(f"- inside the replay, shader cycles per round: bounds {st[24] / r:.0f}, counting {st[25] / r:.0f}, "
               f"compaction {st[26] / r:.0f}, work of the whole workgroup {st[27] / r:.0f}")
-        print(f"- of which: own candidates back from LDS {st[32] / r:.0f}, first barrier {st[33] / r:.0f}, "
+        print(f"- of which: own candidates back from LDS {st[32] / r:.0f}, first barrier (wait for the workers) {st[33] / r:.0f}, "
               f"this wave's share of the pairwise masks {st[34] / r:.0f}, second barrier {st[35] / r:.0f}, "
               f"settling the picks and handing them out {st[36] / r:.0f}")
         print(f"- per round: {st[28] / r:.1f} live candidates, {(M - 1) / r:.1f} picks, "
               f"{st[30] / r:.2f} rounds ended early by a lowered candidate")
         print(f"- rounds by number of live candidates: up to 64: {st[13]}, 65 to {3 * 64}: {st[14]}, "
-              f"one pick at a time: {r - st[13] - st[14]}")
+              f"one pick at a time or none: {r - st[13] - st[14]}")
         print(f"- kernel: {st[16] * 0.01:.1f} us wall, {st[17] * 16 / (st[16] * 10.0):.3f} GHz shader clock\n")
 
 
