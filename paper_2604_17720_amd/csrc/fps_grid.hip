@@ -12,14 +12,20 @@
 // Workgroups meet once per ROUND (fps_exchange.h), and a round can deliver many
 // picks.  The workers apply the picks of a round to their points, all of which
 // are in LDS by then, reduce their slice to its three best points and an upper
-// bound on every other point (the fourth-best value), help the communication
-// wave with the pairwise work of the replay, and wait for the picks.  The
-// communication wave merges the worker waves' results into the workgroup's
-// report, or, when workgroups x worker waves fit the exchange area, passes
-// every wave's result on as a report of its own (more reporting units, more
-// picks per round), exchanges reports with the other workgroups and settles
-// the picks of the round.  Four workgroup barriers per round.  The picks are
+// bound on every other point (the fourth-best value), and help the communication
+// wave with the pairwise work of the replay.  The communication wave merges the
+// worker waves' results into the workgroup's report, or, when workgroups x
+// worker waves fit the exchange area, passes every wave's result on as a report
+// of its own (more reporting units, more picks per round), exchanges reports
+// with the other workgroups and settles the picks of the round.  The picks are
 // exactly those of the one-pick-per-pass loop.
+//
+// With `overlap` (clouds spread over whole workgroups) the communication wave
+// does not wait for the workers' report: the workers first update the three
+// points of their last report with the new picks, which is quick, and the
+// communication wave builds the next round on those while the workers apply the
+// picks to everything else and make their next report.  Five workgroup barriers
+// per round then, four without.
 //
 // Exit: every wait is bounded or ends when the communication wave says so; a
 // workgroup that gives up sets the status word and leaves, and the others then
