@@ -591,13 +591,17 @@ def test_seeded_sweep_of_sizes_batches_and_starts(fb, oracle):
 
 
 @pytest.mark.gpu
-def test_give_up_path_ends_cleanly_and_the_workspace_stays_usable(fb, oracle):
+@pytest.mark.parametrize("n", [60000, 9000])
+def test_give_up_path_ends_cleanly_and_the_workspace_stays_usable(fb, oracle, n):
     """FFPS_ERR_TIMEOUT, forced from the host: with the test knob a workgroup that
     does not find every record at its first look gives up at once; all workgroups
     then leave the kernel in the ordinary way, the status word reads
-    FFPS_ERR_TIMEOUT, and the next call on the same workspace is right again."""
-    x = inputs.make_config(4)[:, :60000].copy()
+    FFPS_ERR_TIMEOUT, and the next call on the same workspace is right again.
+    60,000 points: whole workgroups report and rounds overlap; 9,000 points: every
+    wave reports on its own, one round after the other."""
+    x = inputs.make_config(4)[:, :n].copy()
     M = 1500
+    assert (fb.ffps_describe_plan(1, n, GRID)[2] > fb.ffps_describe_plan(1, n, GRID)[1]) == (n == 9000)
     xd = _dev(x)
     ws = fb.make_workspace(1, x.shape[1], M)
     fb.ffps_exact(xd, M, 0, GRID | fb.FFPS_VARIANT_TEST_NO_WAIT, workspace=ws)
